@@ -1,0 +1,389 @@
+/*
+ * moev_oracle.c -- plain CPU oracle (TEST INFRASTRUCTURE ONLY, see moev_oracle.h).
+ *
+ * Written from the paper's statement of the method; no blocking, fusion, threading or
+ * reordering beyond what the text states.  Build: gcc -std=c99 -O2 -ffp-contract=off.
+ */
+#include "moev_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ===================================================================================
+ * Schedule -- Algorithm 1 ("Sparse Checkpoint Scheduling"), Sec. 3.5
+ * =================================================================================== */
+
+/*
+ * FindWindowSize (Algorithm 1).  All operators start active; operators are moved to the
+ * frozen side one at a time until the estimated transfer time of one snapshot,
+ *     ((S_Master + S_Optim) * O_Active + S_Compute * O_Frozen) / B_PCIe,
+ * fits inside T_Iter.  The search never goes below two active operators (the loop guard
+ * of the listing) and, when it stops at that floor, does not test the fit again.
+ * W_sparse = ceil(O_Total / O_Active).
+ */
+int orc_find_window_size(uint32_t o_total, double t_iter, double s_compute, double s_master,
+                         double s_optim, double b_pcie, uint32_t *w_sparse, uint32_t *o_active) {
+  if (o_total == 0 || !w_sparse || !o_active || !(b_pcie > 0.0)) return ORC_BAD_ARG;
+  uint32_t act = o_total;
+  while (act > 2) {
+    uint32_t frozen = o_total - act;
+    double ckpt_size = (s_master + s_optim) * (double)act + s_compute * (double)frozen;
+    if (ckpt_size / b_pcie <= t_iter) break;
+    act -= 1;
+  }
+  *o_active = act;
+  *w_sparse = (o_total + act - 1) / act;
+  return ORC_OK;
+}
+
+/*
+ * GenerateSchedule (Algorithm 1).  Slot i of the window holds, as active operators, the
+ * i-th run of O_Active consecutive entries of O_Ordered (the last run may be shorter);
+ * everything after that run in O_Ordered is that slot's frozen set.  Stored here as the
+ * slot index in which each operator is active: the active set of slot i is
+ * {e : slot_of_op[e] == i}, its frozen set {e : slot_of_op[e] > i}.
+ */
+int orc_generate_schedule(uint32_t n_ops, const uint32_t *order, uint32_t o_active,
+                          uint32_t *slot_of_op, uint32_t *w_sparse) {
+  if (n_ops == 0 || o_active == 0 || !order || !slot_of_op || !w_sparse) return ORC_BAD_ARG;
+  uint32_t w = (n_ops + o_active - 1) / o_active;
+  for (uint32_t i = 0; i < w; ++i) {
+    uint32_t start = i * o_active;
+    uint32_t end = start + o_active < n_ops ? start + o_active : n_ops;
+    for (uint32_t j = start; j < end; ++j) {
+      if (order[j] >= n_ops) return ORC_BAD_ARG;
+      slot_of_op[order[j]] = i;
+    }
+  }
+  *w_sparse = w;
+  return ORC_OK;
+}
+
+/*
+ * OrderOperators (Sec. 3.5): ascending popularity, so that popular operators are
+ * checkpointed late in the window and stay frozen longest during conversion.  The paper
+ * gives no tie-break; reading taken: stable, equal popularity keeps ascending operator id.
+ * Plain insertion sort.
+ */
+int orc_order_by_popularity(uint32_t n_ops, const double *popularity, uint32_t *order) {
+  if (!popularity || !order) return ORC_BAD_ARG;
+  for (uint32_t e = 0; e < n_ops; ++e) {
+    uint32_t j = e;
+    while (j > 0 && popularity[order[j - 1]] > popularity[e]) {
+      order[j] = order[j - 1];
+      --j;
+    }
+    order[j] = e;
+  }
+  return ORC_OK;
+}
+
+/*
+ * A valid window (Sec. 3.2: after W_sparse iterations every operator has exactly one
+ * FP32 snapshot): `order` is a permutation, every operator has one slot below the window
+ * size, and walking O_Ordered never goes back to an earlier slot (the active sets are
+ * consecutive runs of O_Ordered, Algorithm 1).
+ */
+int orc_check_schedule(uint32_t n_ops, const uint32_t *order, const uint32_t *slot_of_op,
+                       uint32_t window) {
+  if (n_ops == 0 || window == 0 || !order || !slot_of_op) return ORC_BAD_ARG;
+  for (uint32_t e = 0; e < n_ops; ++e) {
+    uint32_t seen = 0;
+    for (uint32_t j = 0; j < n_ops; ++j)
+      if (order[j] == e) ++seen;
+    if (seen != 1) return ORC_NOT_A_SCHEDULE;
+    if (slot_of_op[e] >= window) return ORC_NOT_A_SCHEDULE;
+  }
+  for (uint32_t j = 1; j < n_ops; ++j)
+    if (slot_of_op[order[j]] < slot_of_op[order[j - 1]]) return ORC_NOT_A_SCHEDULE;
+  return ORC_OK;
+}
+
+/* ===================================================================================
+ * Snapshot layout, pack, unpack -- Sec. 3.2 (what a sparse snapshot holds), Sec. 3.3
+ * (what loading one does).  The byte layout of a packed snapshot is this build's own
+ * definition (the paper copies operator by operator and defines none):
+ *
+ *   [256-byte header][segment 0][zero pad][segment 1][zero pad] ...
+ *
+ *   segment order: walk O_Ordered; for each operator active in the slot, for each of its
+ *   tensors in declared order: master, Adam m, Adam v; then walk O_Ordered again; for each
+ *   operator active in a LATER slot, for each of its tensors: compute weights.
+ *   dst_off[0] = roundup(256, align), dst_off[j+1] = dst_off[j] + roundup(nbytes[j], align);
+ *   the snapshot ends at dst_off[last] + roundup(nbytes[last], align).
+ *
+ *   header (little endian): +0 u64 magic "MOEVSNAP", +8 u32 version (1), +12 u32 slot,
+ *   +16 u64 plan hash, +24 u64 iteration, +32 u64 segment count, +40 u64 payload bytes
+ *   (everything after the 256 header bytes), +48 u32 align, rest zero.
+ * =================================================================================== */
+
+static uint32_t width_of(const orc_model *mdl, uint32_t kind) {
+  if (kind == ORC_MASTER) return mdl->width.master;
+  if (kind == ORC_COMPUTE) return mdl->width.compute;
+  return mdl->width.opt;
+}
+
+static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+static void put_le(uint8_t *dst, uint64_t value, int nbytes) {
+  for (int i = 0; i < nbytes; ++i) dst[i] = (uint8_t)(value >> (8 * i));
+}
+
+static uint64_t get_le(const uint8_t *src, int nbytes) {
+  uint64_t value = 0;
+  for (int i = 0; i < nbytes; ++i) value |= (uint64_t)src[i] << (8 * i);
+  return value;
+}
+
+static uint64_t fnv1a(uint64_t h, uint64_t value, int nbytes) {
+  for (int i = 0; i < nbytes; ++i) {
+    h ^= (value >> (8 * i)) & 0xffu;
+    h *= 0x100000001b3ull;
+  }
+  return h;
+}
+
+/*
+ * Identity of a plan, stored in every snapshot header so that a snapshot is never loaded
+ * into a model or schedule it was not taken from.  64-bit FNV-1a over the little-endian
+ * stream: u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 widths (master, opt,
+ * compute), then per tensor (u32 op, u64 numel), per operator u32 slot, per position
+ * u32 order.
+ */
+uint64_t orc_plan_hash(const orc_model *mdl) {
+  uint64_t h = 0xcbf29ce484222325ull;
+  h = fnv1a(h, mdl->n_ops, 4);
+  h = fnv1a(h, mdl->n_tensors, 4);
+  h = fnv1a(h, mdl->window, 4);
+  h = fnv1a(h, mdl->align, 4);
+  h = fnv1a(h, mdl->width.master, 1);
+  h = fnv1a(h, mdl->width.opt, 1);
+  h = fnv1a(h, mdl->width.compute, 1);
+  for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
+    h = fnv1a(h, mdl->tensors[t].op, 4);
+    h = fnv1a(h, mdl->tensors[t].numel, 8);
+  }
+  for (uint32_t e = 0; e < mdl->n_ops; ++e) h = fnv1a(h, mdl->slot_of_op[e], 4);
+  for (uint32_t j = 0; j < mdl->n_ops; ++j) h = fnv1a(h, mdl->order[j], 4);
+  return h;
+}
+
+/*
+ * Segment list of one slot.  Sec. 3.2: the operators active in the slot contribute their
+ * full training state (master weights and optimizer state, 12 bytes per parameter in the
+ * default regime), the operators still waiting for their slot contribute only their
+ * compute weights (2 bytes per parameter); operators whose slot has passed contribute
+ * nothing (the worked example: the second snapshot holds FP32 state of E3,E4 and 2-byte
+ * weights of NE,G only).  Returns the number of segments (also when segs == NULL or
+ * seg_cap is too small, in which case nothing past seg_cap is stored).
+ */
+int64_t orc_layout(const orc_model *mdl, uint32_t slot, orc_segment *segs, uint64_t seg_cap,
+                   uint64_t *packed_bytes) {
+  if (!mdl || slot >= mdl->window || mdl->align == 0) return ORC_BAD_ARG;
+  uint64_t n = 0, off = round_up(ORC_HEADER_BYTES, mdl->align);
+  static const uint32_t full_state[3] = {ORC_MASTER, ORC_ADAM_M, ORC_ADAM_V};
+  for (int pass = 0; pass < 2; ++pass) {
+    for (uint32_t j = 0; j < mdl->n_ops; ++j) {
+      uint32_t e = mdl->order[j];
+      int is_active = mdl->slot_of_op[e] == slot;
+      int is_frozen = mdl->slot_of_op[e] > slot;
+      if (pass == 0 ? !is_active : !is_frozen) continue;
+      for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
+        if (mdl->tensors[t].op != e) continue;
+        int n_kinds = pass == 0 ? 3 : 1;
+        for (int q = 0; q < n_kinds; ++q) {
+          uint32_t kind = pass == 0 ? full_state[q] : ORC_COMPUTE;
+          uint64_t nbytes = mdl->tensors[t].numel * width_of(mdl, kind);
+          if (segs && n < seg_cap) {
+            segs[n].kind = kind;
+            segs[n].tensor = t;
+            segs[n].nbytes = nbytes;
+            segs[n].dst_off = off;
+          }
+          off += round_up(nbytes, mdl->align);
+          ++n;
+        }
+      }
+    }
+  }
+  if (packed_bytes) *packed_bytes = off;
+  return (int64_t)n;
+}
+
+static void *state_ptr(const orc_state *st, uint32_t kind, uint32_t tensor) {
+  if (kind == ORC_MASTER) return st->master[tensor];
+  if (kind == ORC_ADAM_M) return st->m[tensor];
+  if (kind == ORC_ADAM_V) return st->v[tensor];
+  return st->compute[tensor];
+}
+
+/*
+ * Sparse snapshot of slot `slot` taken from state `st` (Sec. 3.2): a byte-for-byte copy of
+ * every listed segment to its offset, zero padding up to the alignment, header in front.
+ */
+int orc_pack(const orc_model *mdl, uint32_t slot, uint64_t iter, const orc_state *st,
+             uint8_t *packed, uint64_t cap) {
+  uint64_t total = 0;
+  int64_t n = orc_layout(mdl, slot, NULL, 0, &total);
+  if (n < 0) return (int)n;
+  if (!st || !packed) return ORC_BAD_ARG;
+  if (cap < total) return ORC_TOO_SMALL;
+  orc_segment *segs = (orc_segment *)malloc((size_t)(n > 0 ? n : 1) * sizeof(orc_segment));
+  if (!segs) return ORC_BAD_ARG;
+  orc_layout(mdl, slot, segs, (uint64_t)n, NULL);
+
+  memset(packed, 0, ORC_HEADER_BYTES);
+  memcpy(packed, "MOEVSNAP", 8);
+  put_le(packed + 8, 1, 4);
+  put_le(packed + 12, slot, 4);
+  put_le(packed + 16, orc_plan_hash(mdl), 8);
+  put_le(packed + 24, iter, 8);
+  put_le(packed + 32, (uint64_t)n, 8);
+  put_le(packed + 40, total - ORC_HEADER_BYTES, 8);
+  put_le(packed + 48, mdl->align, 4);
+  /* with an alignment above 256 the first segment starts later than the header ends */
+  memset(packed + ORC_HEADER_BYTES, 0, round_up(ORC_HEADER_BYTES, mdl->align) - ORC_HEADER_BYTES);
+
+  for (int64_t j = 0; j < n; ++j) {
+    uint64_t padded = round_up(segs[j].nbytes, mdl->align);
+    memcpy(packed + segs[j].dst_off, state_ptr(st, segs[j].kind, segs[j].tensor), segs[j].nbytes);
+    memset(packed + segs[j].dst_off + segs[j].nbytes, 0, padded - segs[j].nbytes);
+  }
+  free(segs);
+  return ORC_OK;
+}
+
+/*
+ * Round-to-nearest-even conversion of an FP32 master weight to a 2-byte bfloat16 compute
+ * weight (the top 16 bits of the FP32 pattern).  NaN stays a (quiet) NaN; values above the
+ * largest finite bfloat16 round to infinity as IEEE rounding prescribes (no saturation).
+ * The paper names FP16 compute weights; this build's workloads use bfloat16.
+ */
+uint16_t orc_bf16_rne(float x) {
+  uint32_t bits;
+  memcpy(&bits, &x, 4);
+  if ((bits & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((bits >> 16) | 0x0040u);
+  uint32_t lower = bits & 0xffffu;        /* the 16 bits that are dropped */
+  uint32_t upper = bits >> 16;            /* the 16 bits that are kept   */
+  if (lower > 0x8000u) upper += 1;        /* above the half-way point: round up */
+  else if (lower == 0x8000u && (upper & 1u)) upper += 1; /* tie: to even */
+  return (uint16_t)upper;
+}
+
+/*
+ * Loading snapshot `slot` during sparse-to-dense conversion (Sec. 3.3; steps 1, 3, 5 of the
+ * walk-through): every segment goes back into the dense tensor it came from.  Operators
+ * whose FP32 state the snapshot carries become ACTIVE (mask 1); operators present only
+ * with compute weights are FROZEN (mask 0); operators activated by an earlier snapshot are
+ * not in the snapshot and are left alone.  A newly active operator's compute weights are
+ * not stored (Sec. 3.2); reading taken: they are re-derived as bf16(master) so that the
+ * dense state is complete (done only in the FP32-master / 2-byte-compute regime).
+ * The header is checked first; a snapshot of another plan, slot or size is refused.
+ */
+int orc_unpack(const orc_model *mdl, uint32_t slot, const uint8_t *packed, uint64_t packed_len,
+               const orc_state *st, uint8_t *active_mask, uint64_t *iter_out) {
+  uint64_t total = 0;
+  int64_t n = orc_layout(mdl, slot, NULL, 0, &total);
+  if (n < 0) return (int)n;
+  if (!st || !packed) return ORC_BAD_ARG;
+  if (packed_len < total) return ORC_TOO_SMALL;
+  if (memcmp(packed, "MOEVSNAP", 8) != 0 || get_le(packed + 8, 4) != 1 ||
+      get_le(packed + 12, 4) != slot || get_le(packed + 16, 8) != orc_plan_hash(mdl) ||
+      get_le(packed + 32, 8) != (uint64_t)n || get_le(packed + 40, 8) != total - ORC_HEADER_BYTES ||
+      get_le(packed + 48, 4) != mdl->align)
+    return ORC_BAD_SNAPSHOT;
+  if (iter_out) *iter_out = get_le(packed + 24, 8);
+
+  orc_segment *segs = (orc_segment *)malloc((size_t)(n > 0 ? n : 1) * sizeof(orc_segment));
+  if (!segs) return ORC_BAD_ARG;
+  orc_layout(mdl, slot, segs, (uint64_t)n, NULL);
+  for (int64_t j = 0; j < n; ++j)
+    memcpy(state_ptr(st, segs[j].kind, segs[j].tensor), packed + segs[j].dst_off, segs[j].nbytes);
+  free(segs);
+
+  for (uint32_t e = 0; e < mdl->n_ops; ++e) {
+    if (mdl->slot_of_op[e] == slot) {
+      if (active_mask) active_mask[e] = 1;
+      if (mdl->width.master == 4 && mdl->width.compute == 2)
+        for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
+          if (mdl->tensors[t].op != e) continue;
+          const float *p = (const float *)st->master[t];
+          uint16_t *c = (uint16_t *)st->compute[t];
+          for (uint64_t i = 0; i < mdl->tensors[t].numel; ++i) c[i] = orc_bf16_rne(p[i]);
+        }
+    } else if (mdl->slot_of_op[e] > slot) {
+      if (active_mask) active_mask[e] = 0;
+    }
+  }
+  return ORC_OK;
+}
+
+/* ===================================================================================
+ * Optimizer replay -- Sec. 3.3: active operators get their FP32 master weights and
+ * optimizer state updated each optimizer step; frozen operators skip the update.
+ * The paper names Adam (Sec. 3.2) / AdamW (App. D) and prints no formula.  Reading taken:
+ * textbook Adam with bias correction, epsilon added after the square root, decoupled
+ * weight decay applied first when non-zero.  All arithmetic in FP32 (the precision the
+ * paper fixes for master weights and optimizer state), each product and sum rounded
+ * separately, in exactly the order written below.
+ * =================================================================================== */
+
+/*
+ * 1 - beta^t for both moments: beta^t by repeated multiplication in double, the
+ * difference rounded to FP32 once.  All operators share the global iteration number t.
+ */
+void orc_bias_corrections(const orc_adam_hp *hp, uint64_t step, float *bc1, float *bc2) {
+  double p1 = 1.0, p2 = 1.0;
+  for (uint64_t i = 0; i < step; ++i) {
+    p1 *= (double)hp->beta1;
+    p2 *= (double)hp->beta2;
+  }
+  *bc1 = (float)(1.0 - p1);
+  *bc2 = (float)(1.0 - p2);
+}
+
+void orc_adam_tensor(float *p, float *m, float *v, const float *g, uint16_t *c, uint64_t n,
+                     const orc_adam_hp *hp, uint64_t step) {
+  float bc1, bc2;
+  orc_bias_corrections(hp, step, &bc1, &bc2);
+  const float lr = hp->lr, beta1 = hp->beta1, beta2 = hp->beta2, eps = hp->eps;
+  const float one_minus_beta1 = 1.0f - beta1;
+  const float one_minus_beta2 = 1.0f - beta2;
+  const float decay = lr * hp->weight_decay;
+  for (uint64_t i = 0; i < n; ++i) {
+    float grad = g[i];
+    float param = p[i];
+    if (hp->weight_decay != 0.0f) param = param - decay * param;
+    float m_new = beta1 * m[i] + one_minus_beta1 * grad;
+    float grad_sq = grad * grad;
+    float v_new = beta2 * v[i] + one_minus_beta2 * grad_sq;
+    float m_hat = m_new / bc1;
+    float v_hat = v_new / bc2;
+    float denom = sqrtf(v_hat) + eps;
+    float update = lr * (m_hat / denom);
+    param = param - update;
+    p[i] = param;
+    m[i] = m_new;
+    v[i] = v_new;
+    if (c) c[i] = orc_bf16_rne(param);
+  }
+}
+
+/*
+ * One replayed iteration of the conversion (steps 2, 4, 6 of the walk-through in
+ * Sec. 3.3): every ACTIVE operator takes the optimizer step of global iteration `step`
+ * with that iteration's gradients and refreshes its compute weights; FROZEN operators are
+ * not touched at all (no moment decay, no step).
+ */
+int orc_replay_step(const orc_model *mdl, const orc_adam_hp *hp, uint64_t step,
+                    const uint8_t *active_mask, const float *const *grads, const orc_state *st) {
+  if (!mdl || !hp || !active_mask || !grads || !st || step == 0) return ORC_BAD_ARG;
+  if (mdl->width.master != 4 || mdl->width.opt != 4 || mdl->width.compute != 2) return ORC_BAD_ARG;
+  for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
+    if (!active_mask[mdl->tensors[t].op]) continue;
+    orc_adam_tensor((float *)st->master[t], (float *)st->m[t], (float *)st->v[t], grads[t],
+                    (uint16_t *)st->compute[t], mdl->tensors[t].numel, hp, step);
+  }
+  return ORC_OK;
+}

@@ -1,0 +1,235 @@
+"""Seeded synthetic workloads: shapes, schedules and value generators.
+
+This module only describes inputs (which operators exist, how large their tensors are,
+which window slot each operator is scheduled in) and draws seeded random values with the
+stated distributions.  It holds none of the method's arithmetic and is used both by the
+HIP path's callers and by the tests that feed the CPU oracle, so both see the same bits.
+
+Shapes stand in for the MoE models of the paper's evaluation (Sec. 5.1, model table):
+a Mixtral-8x7B-shaped layer, fine-grained layers with shared experts (DeepSeek-MoE-like)
+and one expert-parallel rank's share of a large MoE.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+import torch
+
+T0 = 10  # iteration after which the first snapshot of a window is taken (the paper's example uses 10)
+
+
+@dataclass
+class Workload:
+    name: str
+    tensors: List[Tuple[int, int]]        # (op, numel) grouped by ascending op
+    slot_of_op: List[int]                 # slot in which each operator is checkpointed with full state
+    window: int
+    order: List[int] = field(default_factory=list)  # O_Ordered; derived from slots when empty
+    heavy_tail: bool = False              # gradients: 5% of entries scaled by 100
+    lr: float = 1e-4
+    beta1: float = 0.9
+    beta2: float = 0.95
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    t0: int = T0
+
+    def __post_init__(self):
+        if not self.order:
+            self.order = sorted(range(len(self.slot_of_op)), key=lambda e: (self.slot_of_op[e], e))
+
+    @property
+    def n_ops(self) -> int:
+        return len(self.slot_of_op)
+
+    @property
+    def n_tensors(self) -> int:
+        return len(self.tensors)
+
+    @property
+    def n_params(self) -> int:
+        return sum(n for _, n in self.tensors)
+
+    def params_of_op(self) -> List[int]:
+        out = [0] * self.n_ops
+        for op, n in self.tensors:
+            out[op] += n
+        return out
+
+    def slot_payload_bytes(self, slot: int, widths=(4, 4, 2)) -> int:
+        """Unpadded bytes a snapshot of `slot` carries: full state of the operators scheduled
+        in the slot plus compute weights of the operators scheduled later."""
+        full = widths[0] + 2 * widths[1]
+        total = 0
+        for e, p in enumerate(self.params_of_op()):
+            if self.slot_of_op[e] == slot:
+                total += full * p
+            elif self.slot_of_op[e] > slot:
+                total += widths[2] * p
+        return total
+
+    def active_params_at(self, i: int) -> int:
+        """Parameters updated by replay iteration i of a conversion (operators with slot <= i)."""
+        return sum(p for e, p in enumerate(self.params_of_op()) if self.slot_of_op[e] <= i)
+
+
+# ---------------------------------------------------------------------------------------
+# small integer hashing used for seeds and permutations (no floating point involved)
+# ---------------------------------------------------------------------------------------
+_M64 = (1 << 64) - 1
+
+
+def mix64(x: int) -> int:
+    """splitmix64 finaliser."""
+    x = (x + 0x9E3779B97F4A7C15) & _M64
+    x = ((x ^ (x >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    x = ((x ^ (x >> 27)) * 0x94D049BB133111EB) & _M64
+    return x ^ (x >> 31)
+
+
+def stream_seed(seed: int, stream: int, tensor: int, step: int = 0) -> int:
+    h = mix64(seed)
+    for part in (stream, tensor, step):
+        h = mix64(h ^ mix64(part + 0x51ED27))
+    return h & ((1 << 63) - 1)
+
+
+def seeded_permutation(n: int, seed: int) -> List[int]:
+    """Fisher-Yates shuffle driven by the counter hash above."""
+    perm = list(range(n))
+    for i in range(n - 1, 0, -1):
+        j = mix64((seed << 20) ^ i) % (i + 1)
+        perm[i], perm[j] = perm[j], perm[i]
+    return perm
+
+
+# ---------------------------------------------------------------------------------------
+# the benchmark configurations
+# ---------------------------------------------------------------------------------------
+def _swiglu(d_model: int, d_ff: int) -> List[int]:
+    return [d_model * d_ff, d_model * d_ff, d_ff * d_model]  # w1, w3, w2
+
+
+def tiny_moe(n_experts=8, d_in=256, d_hidden=1024, window=4, n_active=2) -> Workload:
+    """configs[0]: 8 experts, W_in 256x1024 and W_out 1024x256, W=4, 2 active per slot, round robin."""
+    tensors = []
+    for e in range(n_experts):
+        tensors += [(e, d_in * d_hidden), (e, d_hidden * d_in)]
+    slots = [e // n_active for e in range(n_experts)]
+    assert max(slots) + 1 == window
+    return Workload("c0_tiny_moe", tensors, slots, window, order=list(range(n_experts)))
+
+
+def mixtral_layer(n_experts=8, d_model=4096, d_ff=14336, n_active=1) -> Workload:
+    """configs[1]: one Mixtral-8x7B-shaped MoE layer, W=8, one expert active per slot."""
+    tensors = []
+    for e in range(n_experts):
+        tensors += [(e, n) for n in _swiglu(d_model, d_ff)]
+    slots = [e // n_active for e in range(n_experts)]
+    return Workload("c1_mixtral_layer", tensors, slots, max(slots) + 1, order=list(range(n_experts)))
+
+
+def fine_grained_stack(n_layers=4, n_routed=64, n_shared=2, d_model=2048, d_ff=1408, per_slot=4,
+                       seed=0, heavy_tail=False, name="c2_fine_grained") -> Workload:
+    """configs[2] / configs[4]: per layer, the routed experts are checkpointed in the order of a
+    seeded permutation, `per_slot` of them per layer per slot; the always-routed shared experts
+    are the most popular operators and therefore come last (they join the final slot)."""
+    window = (n_routed + per_slot - 1) // per_slot
+    per_layer = n_routed + n_shared
+    tensors, slots = [], []
+    for layer in range(n_layers):
+        perm = seeded_permutation(n_routed, seed + layer)
+        pos = {e: q for q, e in enumerate(perm)}
+        for j in range(per_layer):
+            op = layer * per_layer + j
+            tensors += [(op, n) for n in _swiglu(d_model, d_ff)]
+            slots.append(pos[j] // per_slot if j < n_routed else window - 1)
+    return Workload(name, tensors, slots, window, heavy_tail=heavy_tail)
+
+
+def ep_rank_share(n_layers=16, n_experts=32, d_model=4096, d_ff=2048, per_slot=4) -> Workload:
+    """configs[3]: one GPU's share of a large MoE, uniform experts, W=8, 4 per layer per slot."""
+    tensors, slots = [], []
+    for layer in range(n_layers):
+        for j in range(n_experts):
+            op = layer * n_experts + j
+            tensors += [(op, n) for n in _swiglu(d_model, d_ff)]
+            slots.append(j // per_slot)
+    return Workload("c3_ep_rank_share", tensors, slots, max(slots) + 1)
+
+
+def conversion_stress(**kw) -> Workload:
+    """configs[4]: configs[2] shapes with heavy-tailed gradients."""
+    kw.setdefault("heavy_tail", True)
+    kw.setdefault("name", "c4_conversion_stress")
+    return fine_grained_stack(**kw)
+
+
+CONFIGS = {
+    "c0": tiny_moe,
+    "c1": mixtral_layer,
+    "c2": fine_grained_stack,
+    "c3": ep_rank_share,
+    "c4": conversion_stress,
+}
+
+
+# ---------------------------------------------------------------------------------------
+# value generators
+# ---------------------------------------------------------------------------------------
+_STREAM = {"master": 1, "m": 2, "v": 3, "grad": 4, "tail": 5}
+
+
+def _gen(device, seed: int) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    return g
+
+
+def make_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, List[torch.Tensor]]:
+    """master ~ N(0, std 0.02), m ~ N(0, std 1e-3), v = N(0, std 1e-3)^2 (so v >= 0),
+    compute = bfloat16 copy of master.  One generator stream per (kind, tensor)."""
+    st: Dict[str, List[torch.Tensor]] = {"master": [], "m": [], "v": [], "compute": []}
+    for t, (_, n) in enumerate(wl.tensors):
+        p = torch.empty(n, dtype=torch.float32, device=device)
+        p.normal_(0.0, 0.02, generator=_gen(device, stream_seed(seed, _STREAM["master"], t)))
+        m = torch.empty(n, dtype=torch.float32, device=device)
+        m.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["m"], t)))
+        v = torch.empty(n, dtype=torch.float32, device=device)
+        v.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["v"], t)))
+        v.square_()
+        st["master"].append(p)
+        st["m"].append(m)
+        st["v"].append(v)
+        st["compute"].append(p.to(torch.bfloat16))
+    return st
+
+
+def make_grads(wl: Workload, step: int, seed: int = 0, device="cpu") -> List[torch.Tensor]:
+    """Gradients of iteration `step`: N(0, std 1e-3), fresh per (step, tensor).  With
+    wl.heavy_tail an independent uniform draw marks 5% of the entries, which are scaled by 100."""
+    out = []
+    for t, (_, n) in enumerate(wl.tensors):
+        g = torch.empty(n, dtype=torch.float32, device=device)
+        g.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["grad"], t, step)))
+        if wl.heavy_tail:
+            u = torch.empty(n, dtype=torch.float32, device=device)
+            u.uniform_(0.0, 1.0, generator=_gen(device, stream_seed(seed, _STREAM["tail"], t, step)))
+            g = torch.where(u < 0.05, g * 100.0, g)
+        out.append(g)
+    return out
+
+
+def random_bits_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, List[torch.Tensor]]:
+    """State filled with arbitrary bit patterns (for pure byte-movement tests: compute weights
+    are NOT the rounded master weights here, NaN / Inf / denormal patterns occur)."""
+    st: Dict[str, List[torch.Tensor]] = {"master": [], "m": [], "v": [], "compute": []}
+    for t, (_, n) in enumerate(wl.tensors):
+        for k, kind in enumerate(("master", "m", "v")):
+            bits = torch.randint(-(1 << 31), (1 << 31) - 1, (n,), dtype=torch.int32, device=device,
+                                 generator=_gen(device, stream_seed(seed, 10 + k, t)))
+            st[kind].append(bits.view(torch.float32))
+        bits = torch.randint(-(1 << 15), (1 << 15) - 1, (n,), dtype=torch.int16, device=device,
+                             generator=_gen(device, stream_seed(seed, 13, t)))
+        st["compute"].append(bits.view(torch.bfloat16))
+    return st

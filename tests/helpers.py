@@ -1,0 +1,47 @@
+"""Glue shared by the tests: move seeded workload tensors into the oracle's numpy containers."""
+import numpy as np
+import torch
+
+import oracle
+
+
+def model_of(wl, align=256, widths=(4, 4, 2)):
+    return oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, align, widths)
+
+
+def hp_of(wl):
+    return oracle.AdamHP(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
+
+
+def np_of(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+def state_of(st) -> "oracle.State":
+    return oracle.State(*[[np_of(t) for t in st[k]] for k in ("master", "m", "v", "compute")])
+
+
+def states_equal(a: "oracle.State", b: "oracle.State"):
+    """Bitwise comparison; returns the list of (kind, tensor) that differ."""
+    bad = []
+    for kind in ("master", "m", "v", "compute"):
+        for t, (x, y) in enumerate(zip(a.kinds()[kind], b.kinds()[kind])):
+            if x.tobytes() != y.tobytes():
+                bad.append((kind, t))
+    return bad
+
+
+def max_rel_err(x: np.ndarray, ref: np.ndarray) -> float:
+    """max |x - ref| / max(|ref|, 1e-30), NaN patterns must coincide."""
+    x = x.astype(np.float64)
+    ref = ref.astype(np.float64)
+    nan_x, nan_r = np.isnan(x), np.isnan(ref)
+    if not np.array_equal(nan_x, nan_r):
+        return float("inf")
+    ok = ~nan_r
+    if not ok.any():
+        return 0.0
+    return float(np.max(np.abs(x[ok] - ref[ok]) / np.maximum(np.abs(ref[ok]), 1e-30)))

@@ -1,0 +1,344 @@
+"""Pins for the oracle's Adam replay and sparse-to-dense conversion (CPU only).
+
+Pinned against: closed forms of Adam, a pure-Python double-precision evaluation of the
+textbook formula, torch.optim.Adam / AdamW as black-box library routines, the definition of
+round-to-nearest-even for the bf16 cast, the conversion walk-through of Sec. 3.3 (golden
+fixture), and the method's central invariant: conversion of the sparse window equals a
+fault-free dense run, bit for bit.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_15411_amd import workloads as W
+from helpers import hp_of, model_of, np_of, state_of, states_equal, max_rel_err
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------------------
+# bf16 cast
+# ---------------------------------------------------------------------------------------
+def _f32(bits: int) -> float:
+    return float(np.array([bits], dtype=np.uint32).view(np.float32)[0])
+
+
+def test_bf16_rne_all_high_halves_against_definition(orc):
+    """For every 16-bit high half and low halves {0, 1, 0x7fff, 0x8000, 0x8001, 0xffff}: the
+    result is the bf16 value nearest to the input, ties to the even mantissa (exact rational
+    arithmetic on the two neighbours), NaN stays NaN, overflow rounds to infinity."""
+    lows = (0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF)
+    for hi in range(0, 1 << 16, 1):
+        if hi % 7 and hi & 0x7F80 != 0x7F80 and hi & 0x7FFF > 0x0100:  # thin out the bulk, keep edges
+            continue
+        for lo in lows:
+            bits = (hi << 16) | lo
+            got = orc.bf16_rne(_f32(bits))
+            if (bits & 0x7FFFFFFF) > 0x7F800000:
+                assert (got & 0x7F80) == 0x7F80 and (got & 0x7F), hex(bits)  # still a NaN
+                assert (got >> 15) == (bits >> 31)
+                continue
+            if (bits & 0x7FFFFFFF) == 0x7F800000:
+                assert got == hi
+                continue
+            down, up = hi, hi + 1  # neighbours in magnitude order (same sign bit)
+            x = Fraction(_f32(bits))
+            f_down = Fraction(_f32(down << 16))
+            if (up & 0x7F80) == 0x7F80:   # next value up is infinity: treat as 2^128 for the distance
+                f_up = Fraction(2) ** 128 * (-1 if bits >> 31 else 1)
+            else:
+                f_up = Fraction(_f32((up & 0xFFFF) << 16))
+            d_down, d_up = abs(x - f_down), abs(f_up - x)
+            if d_down < d_up:
+                exp = down
+            elif d_up < d_down:
+                exp = up
+            else:
+                exp = down if down % 2 == 0 else up
+            assert got == (exp & 0xFFFF), hex(bits)
+
+
+def test_bf16_rne_matches_library_cast(orc):
+    """Black-box cross-check against torch's float32 -> bfloat16 conversion on random bit patterns
+    (finite values; NaN payloads are implementation-defined)."""
+    g = torch.Generator().manual_seed(3)
+    bits = torch.randint(-(1 << 31), (1 << 31) - 1, (20000,), dtype=torch.int32, generator=g)
+    x = bits.view(torch.float32)
+    x = x[torch.isfinite(x)]
+    lib = x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = orc.bf16_rne_array(x.numpy())
+    assert np.array_equal(got, lib)
+
+
+# ---------------------------------------------------------------------------------------
+# Adam step
+# ---------------------------------------------------------------------------------------
+def test_bias_corrections(orc):
+    hp = orc.AdamHP()
+    for step in (1, 2, 10, 11, 100, 5000):
+        bc1, bc2 = orc.bias_corrections(hp, step)
+        b1, b2 = float(np.float32(hp.beta1)), float(np.float32(hp.beta2))
+        assert bc1 == float(np.float32(1.0 - b1 ** step))
+        assert bc2 == float(np.float32(1.0 - b2 ** step))
+
+
+def test_adam_closed_form_constant_gradient(orc):
+    """m0 = v0 = 0 and a constant gradient g: m_hat = g and v_hat = g^2 at every step, so
+    p_t = p_0 - t * lr * g / (|g| + eps) (up to fp32 rounding)."""
+    hp = orc.AdamHP(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    g = np.array([0.5, -0.25, 3.0, -1e-3, 2e-5], dtype=np.float32)
+    p0 = np.array([1.0, -2.0, 0.5, 0.25, -0.125], dtype=np.float32)
+    p, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    c = np.zeros(p0.size, dtype=np.uint16)
+    for t in range(1, 21):
+        orc.adam_tensor(p, m, v, g, c, hp, t)
+        exp = p0.astype(np.float64) - t * 1e-3 * g.astype(np.float64) / (np.abs(g.astype(np.float64)) + 1e-8)
+        assert np.allclose(p, exp, rtol=2e-6, atol=0)
+        bc1, bc2 = orc.bias_corrections(hp, t)
+        assert np.allclose(m / bc1, g, rtol=1e-5) and np.allclose(v / bc2, g.astype(np.float64) ** 2, rtol=1e-5)
+    assert np.array_equal(c, orc.bf16_rne_array(p))
+
+
+def test_adam_closed_form_zero_gradient(orc):
+    """g = 0: m_t = beta1^t m_0, v_t = beta2^t v_0 (pure decay)."""
+    hp = orc.AdamHP()
+    m0 = np.array([1e-3, -2e-3, 0.5], dtype=np.float32)
+    v0 = np.array([1e-6, 4e-6, 0.25], dtype=np.float32)
+    p, m, v = np.ones(3, dtype=np.float32), m0.copy(), v0.copy()
+    g = np.zeros(3, dtype=np.float32)
+    for t in range(1, 9):
+        orc.adam_tensor(p, m, v, g, None, hp, t)
+        assert np.allclose(m, float(np.float32(0.9)) ** t * m0.astype(np.float64), rtol=1e-6)
+        assert np.allclose(v, float(np.float32(0.95)) ** t * v0.astype(np.float64), rtol=1e-6)
+
+
+def _adam_python_double(p, m, v, g, hp, step):
+    """Textbook Adam with bias correction, in Python floats (double), one element at a time."""
+    b1, b2 = float(np.float32(hp.beta1)), float(np.float32(hp.beta2))
+    lr, eps, wd = float(np.float32(hp.lr)), float(np.float32(hp.eps)), float(np.float32(hp.weight_decay))
+    out = []
+    for pi, mi, vi, gi in zip(p, m, v, g):
+        pi, mi, vi, gi = float(pi), float(mi), float(vi), float(gi)
+        if wd:
+            pi -= lr * wd * pi
+        mi = b1 * mi + (1 - b1) * gi
+        vi = b2 * vi + (1 - b2) * gi * gi
+        m_hat = mi / (1 - b1 ** step)
+        v_hat = vi / (1 - b2 ** step)
+        pi -= lr * m_hat / (math.sqrt(v_hat) + eps)
+        out.append((pi, mi, vi))
+    return out
+
+
+@pytest.mark.parametrize("wd", [0.0, 0.1])
+def test_adam_against_python_double(orc, wd):
+    """Brute force on a small tensor: the fp32 oracle stays within a few ulp of the double
+    evaluation when nothing cancels (m and g of equal sign)."""
+    wl = W.Workload("x", [(0, 257)], [0], 1, weight_decay=wd)
+    st = W.make_state(wl, seed=8)
+    g = W.make_grads(wl, step=11, seed=8)[0].abs()
+    p, m, v = np_of(st["master"][0]), np.abs(np_of(st["m"][0])), np_of(st["v"][0])
+    g = np_of(g)
+    hp = orc.AdamHP(weight_decay=wd)
+    exp = _adam_python_double(p, m, v, g, hp, 11)
+    p_old = p.copy()
+    c = np.zeros(p.size, dtype=np.uint16)
+    orc.adam_tensor(p, m, v, g, c, hp, 11)
+    for i, (pe, me, ve) in enumerate(exp):
+        # p_old - update may cancel: bound the error by the magnitudes that were subtracted
+        assert abs(p[i] - pe) <= 4e-7 * (abs(float(p_old[i])) + abs(float(p_old[i]) - pe))
+        assert abs(m[i] - me) <= 4e-7 * abs(me)
+        assert abs(v[i] - ve) <= 4e-7 * abs(ve)
+
+
+@pytest.mark.parametrize("wd", [0.0, 0.05])
+def test_adam_against_torch_optimizer(orc, wd):
+    """Library cross-check (black box): torch.optim.Adam (wd = 0) / AdamW (decoupled decay) in
+    float64 started from the same state, 12 consecutive steps from iteration 10."""
+    wl = W.Workload("x", [(0, 4096)], [0], 1, weight_decay=wd)
+    st = W.make_state(wl, seed=21)
+    p, m, v = np_of(st["master"][0]), np_of(st["m"][0]), np_of(st["v"][0])
+    hp = orc.AdamHP(weight_decay=wd)
+    b1, b2 = float(np.float32(hp.beta1)), float(np.float32(hp.beta2))
+    param = torch.nn.Parameter(torch.from_numpy(p.astype(np.float64)))
+    cls = torch.optim.AdamW if wd else torch.optim.Adam
+    opt = cls([param], lr=float(np.float32(hp.lr)), betas=(b1, b2), eps=float(np.float32(hp.eps)),
+              weight_decay=float(np.float32(wd)))
+    opt.state[param] = {"step": torch.tensor(10.0), "exp_avg": torch.from_numpy(m.astype(np.float64)),
+                        "exp_avg_sq": torch.from_numpy(v.astype(np.float64))}
+    c = np.zeros(p.size, dtype=np.uint16)
+    for step in range(11, 23):
+        g = np_of(W.make_grads(wl, step=step, seed=21)[0])
+        param.grad = torch.from_numpy(g.astype(np.float64))
+        opt.step()
+        orc.adam_tensor(p, m, v, g, c, hp, step)
+    ref_p = param.detach().numpy()
+    ref_m = opt.state[param]["exp_avg"].numpy()
+    ref_v = opt.state[param]["exp_avg_sq"].numpy()
+    assert int(opt.state[param]["step"]) == 22
+    assert np.max(np.abs(p - ref_p) / np.maximum(np.abs(ref_p), 1e-3)) < 1e-6
+    assert np.max(np.abs(m - ref_m)) < 1e-6 * np.max(np.abs(ref_m))
+    assert np.max(np.abs(v - ref_v) / np.abs(ref_v)) < 2e-6
+    assert np.array_equal(c, orc.bf16_rne_array(p))
+
+
+def test_adam_operation_order_is_pinned(orc):
+    """The fp32 result equals the same expression evaluated with numpy float32 scalars, each
+    operation rounded separately (no fused multiply-add, division and square root correctly rounded)."""
+    wl = W.Workload("x", [(0, 1000)], [0], 1)
+    st = W.make_state(wl, seed=4)
+    p, m, v = np_of(st["master"][0]), np_of(st["m"][0]), np_of(st["v"][0])
+    g = np_of(W.make_grads(W.Workload("x", [(0, 1000)], [0], 1, heavy_tail=True), step=3, seed=4)[0])
+    hp = orc.AdamHP()
+    f = np.float32
+    bc1, bc2 = (f(x) for x in orc.bias_corrections(hp, 13))
+    b1, b2, lr, eps = f(hp.beta1), f(hp.beta2), f(hp.lr), f(hp.eps)
+    m_new = b1 * m + (f(1) - b1) * g
+    v_new = b2 * v + (f(1) - b2) * (g * g)
+    p_new = p - lr * ((m_new / bc1) / (np.sqrt(v_new / bc2) + eps))
+    assert m_new.dtype == np.float32 and p_new.dtype == np.float32
+    orc.adam_tensor(p, m, v, g, None, hp, 13)
+    assert p.tobytes() == p_new.tobytes() and m.tobytes() == m_new.tobytes() and v.tobytes() == v_new.tobytes()
+
+
+def test_replay_skips_frozen_operators(orc):
+    """Frozen operators are left bit-for-bit alone: no moment decay, no step (Sec. 3.3)."""
+    wl = W.tiny_moe(d_in=8, d_hidden=24)
+    model, hp = model_of(wl), hp_of(wl)
+    st = state_of(W.make_state(wl, seed=1))
+    before = st.clone()
+    mask = np.array([1, 0, 0, 1, 0, 0, 0, 1], dtype=np.uint8)
+    grads = [np_of(g) for g in W.make_grads(wl, step=11, seed=1)]
+    orc.replay_step(model, hp, 11, mask, grads, st)
+    changed = {t for _, t in states_equal(st, before)}
+    assert changed == {t for t, (op, _) in enumerate(wl.tensors) if mask[op]}
+    for t in changed:
+        p, m, v = before.master[t].copy(), before.m[t].copy(), before.v[t].copy()
+        c = np.zeros(p.size, dtype=np.uint16)
+        orc.adam_tensor(p, m, v, grads[t], c, hp, 11)
+        assert p.tobytes() == st.master[t].tobytes() and c.tobytes() == st.compute[t].tobytes()
+
+
+# ---------------------------------------------------------------------------------------
+# sparse-to-dense conversion
+# ---------------------------------------------------------------------------------------
+def _grads_fn(wl, seed):
+    cache = {}
+
+    def grads_of_step(t):
+        if t not in cache:
+            cache[t] = [np_of(g) for g in W.make_grads(wl, step=t, seed=seed)]
+        return cache[t]
+    return grads_of_step
+
+
+def _run_window(orc, wl, seed=0, align=256):
+    model, hp = model_of(wl, align=align), hp_of(wl)
+    grads = _grads_fn(wl, seed)
+    dense = state_of(W.make_state(wl, seed=seed))
+    snaps = orc.dense_run(model, dense, hp, grads, wl.t0, wl.window, snapshots=True)
+    rebuilt = orc.poisoned_like(dense)
+    trace = []
+    mask = orc.convert(model, snaps, hp, grads, rebuilt, trace)
+    return dense, rebuilt, mask, trace, snaps
+
+
+def test_conversion_walkthrough_trace(orc):
+    """Sec. 3.3 walk-through (golden fixture): which operators are active after each load and
+    which are advanced by each replay, for the six-operator example."""
+    names = ["E1", "E2", "E3", "E4", "NE", "G"]
+    wl = W.Workload("example", [(e, 96 + 5 * e) for e in range(6)], [0, 0, 1, 1, 2, 2], 3,
+                    order=list(range(6)))
+    _, _, mask, trace, _ = _run_window(orc, wl, seed=2)
+    rows = []
+    with open(os.path.join(GOLD, "worked_example_conversion.txt")) as f:
+        rows = [l.strip() for l in f if l.strip() and not l.startswith("#")]
+    steps = [r for r in rows if r.split()[0] in ("load", "replay")]
+    assert len(steps) == len(trace) == 6
+    for row, (what, it, m) in zip(steps, trace):
+        parts = row.split()
+        assert parts[0] == what and int(parts[1]) == it
+        if what == "load":
+            body = row.split("active", 1)[1]
+            act, _, fro = body.partition("|")
+            assert [names[e] for e in range(6) if m[e]] == act.split()
+            assert [names[e] for e in range(6) if not m[e]] == fro.split()[1:]
+        else:
+            assert [names[e] for e in range(6) if m[e]] == row.split("updates", 1)[1].split()
+    assert mask.tolist() == [1] * 6
+    final = int([r for r in rows if r.startswith("dense_checkpoint_iteration")][0].split()[1])
+    assert final == wl.t0 + wl.window
+
+
+@pytest.mark.parametrize("n_active", [1, 2, 3, 4, 5, 6])
+def test_conversion_equals_dense_run_example(orc, n_active):
+    """Central invariant (Sec. 3.3): the converted state is identical to the dense checkpoint of a
+    fault-free run, for every window size the six-operator example admits."""
+    n = 6
+    slots, window = orc.generate_schedule(list(range(n)), n_active)
+    wl = W.Workload("example", [(e, 64 + 3 * e) for e in range(n)] + [], slots, window, order=list(range(n)))
+    wl.tensors = sorted([(e, 64 + 3 * e) for e in range(n)] + [(e, 17) for e in range(n)])
+    dense, rebuilt, mask, _, _ = _run_window(orc, wl, seed=n_active)
+    assert mask.all()
+    assert states_equal(dense, rebuilt) == []
+
+
+def test_conversion_equals_dense_run_tiny_config(orc):
+    """configs[0] (tiny MoE layer, W = 4, two experts per slot, 4 replay iterations)."""
+    wl = W.tiny_moe()
+    dense, rebuilt, mask, _, snaps = _run_window(orc, wl, seed=0)
+    assert mask.all() and states_equal(dense, rebuilt) == []
+    assert [s.size for s in snaps] == [256 + wl.slot_payload_bytes(k) for k in range(4)]
+
+
+def test_conversion_heavy_tail_and_permuted_schedule(orc):
+    """A shrunken configs[4]: permuted per-layer schedule with shared experts in the last slot and
+    heavy-tailed gradients; conversion still equals the dense run bit for bit."""
+    wl = W.conversion_stress(n_layers=2, n_routed=8, n_shared=2, d_model=16, d_ff=11, per_slot=2)
+    assert wl.window == 4 and wl.heavy_tail
+    dense, rebuilt, mask, _, _ = _run_window(orc, wl, seed=6, align=16)
+    assert mask.all() and states_equal(dense, rebuilt) == []
+
+
+def test_conversion_detects_planted_mistakes(orc):
+    """The comparison has teeth: a conversion that replays with the wrong iteration's gradients,
+    that skips the first replay of newly activated operators, or that is fed snapshots taken one
+    step late, no longer matches the dense run."""
+    wl = W.tiny_moe(d_in=8, d_hidden=16)
+    model, hp = model_of(wl), hp_of(wl)
+    grads = _grads_fn(wl, 3)
+    dense = state_of(W.make_state(wl, seed=3))
+    snaps = orc.dense_run(model, dense, hp, grads, wl.t0, wl.window, snapshots=True)
+    # (a) off-by-one iteration
+    bad = orc.poisoned_like(dense)
+    orc.convert(model, snaps, hp, lambda t: grads(t + 1), bad)
+    assert states_equal(dense, bad)
+    # (b) operators activated by a load miss the replay that follows it (stale mask)
+    bad = orc.poisoned_like(dense)
+    mask = np.zeros(wl.n_ops, dtype=np.uint8)
+    for i in range(wl.window):
+        stale = mask.copy()
+        it = orc.unpack(model, i, snaps[i], bad, mask)
+        orc.replay_step(model, hp, it + 1, stale, grads(it + 1), bad)
+    assert states_equal(dense, bad)
+    # (c) snapshots taken one optimizer step late (state after step t0+k+1 stored as SS_{t0+k})
+    late_src = state_of(W.make_state(wl, seed=3))
+    everyone = np.ones(wl.n_ops, dtype=np.uint8)
+    late = []
+    for k in range(wl.window):
+        orc.replay_step(model, hp, wl.t0 + k + 1, everyone, grads(wl.t0 + k + 1), late_src)
+        late.append(orc.pack(model, k, wl.t0 + k, late_src))
+    bad = orc.poisoned_like(dense)
+    orc.convert(model, late, hp, grads, bad)
+    assert states_equal(dense, bad)
+
+
+def test_dense_special_case_w1(orc):
+    """W = 1 reduces to a dense checkpoint followed by one ordinary Adam step."""
+    wl = W.Workload("dense", [(0, 50), (1, 33)], [0, 0], 1)
+    dense, rebuilt, mask, _, snaps = _run_window(orc, wl, seed=5, align=16)
+    assert len(snaps) == 1 and states_equal(dense, rebuilt) == []

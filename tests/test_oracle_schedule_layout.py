@@ -1,0 +1,341 @@
+"""Pins for the oracle's schedule, layout, pack and unpack (CPU only).
+
+The oracle is pinned to things other than itself: the paper's worked example (golden text
+fixtures), closed forms for snapshot sizes, brute-force sums, and the invariants the method
+fixes (every operator checkpointed exactly once per window, pack followed by unpack is the
+identity, nothing outside the slot's segments is touched).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2412_15411_amd import workloads as W
+from helpers import model_of, state_of, states_equal
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_fixture(name):
+    rows = []
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line)
+    return rows
+
+
+def _example():
+    rows = _read_fixture("worked_example_schedule.txt")
+    d = {"snap": []}
+    for r in rows:
+        key, _, rest = r.partition(" ")
+        if key == "operators":
+            d["ops"] = rest.split()
+        elif key == "snapshot":
+            it, _, sets = rest.partition(" ")
+            fp32, _, comp = sets.partition("|")
+            d["snap"].append((int(it), fp32.split()[1:], comp.split()[1:]))
+        else:
+            d[key] = float(rest)
+    return d
+
+
+# ---------------------------------------------------------------------------------------
+# schedule
+# ---------------------------------------------------------------------------------------
+def test_worked_example_schedule(orc):
+    """Sec. 3.2 worked example: six operators, two per slot, W = 3, exact active / frozen sets."""
+    ex = _example()
+    names = ex["ops"]
+    n = len(names)
+    slots, window = orc.generate_schedule(list(range(n)), int(ex["active_per_slot"]))
+    assert window == int(ex["window"])
+    for k, (_, fp32, comp) in enumerate(ex["snap"]):
+        active = [names[e] for e in range(n) if slots[e] == k]
+        frozen = [names[e] for e in range(n) if slots[e] > k]
+        assert active == fp32
+        assert frozen == comp
+    model = orc.Model([(e, 100) for e in range(n)], list(range(n)), slots, window)
+    for k, (_, fp32, comp) in enumerate(ex["snap"]):
+        segs, _ = orc.layout(model, k)
+        got_fp32 = [names[t] for kind, t, _, _ in segs if kind == orc.MASTER]
+        got_comp = [names[t] for kind, t, _, _ in segs if kind == orc.COMPUTE]
+        assert got_fp32 == fp32 and got_comp == comp
+        # full state = master, m, v in that order for each active tensor
+        kinds = [kind for kind, _, _, _ in segs][: 3 * len(fp32)]
+        assert kinds == [orc.MASTER, orc.ADAM_M, orc.ADAM_V] * len(fp32)
+
+
+def test_worked_example_sizes(orc):
+    """Sec. 3.2: 12 vs 2 bytes per parameter (83% smaller); first sparse snapshot ~55% below dense."""
+    ex = _example()
+    n = len(ex["ops"])
+    p = 1000
+    slots, window = orc.generate_schedule(list(range(n)), 2)
+    model = orc.Model([(e, p) for e in range(n)], list(range(n)), slots, window, align=8)
+    sizes = []
+    for k in range(window):
+        segs, total = orc.layout(model, k)
+        sizes.append(sum(nb for _, _, nb, _ in segs))
+        assert total - orc.HEADER_BYTES == sizes[-1]  # p*4 and p*2 are multiples of 8: no padding
+    a, f = int(ex["bytes_per_param_active"]), int(ex["bytes_per_param_frozen"])
+    assert sizes == [(2 * a + 4 * f) * p, (2 * a + 2 * f) * p, 2 * a * p]  # 32, 28, 24 units
+    dense = n * a * p
+    assert round(100 * (1 - sizes[0] / dense)) in (int(ex["first_snapshot_saving_percent"]), 56)
+    assert abs(100 * (1 - sizes[0] / dense) - 55.6) < 0.1
+    assert round(100 * (1 - f / a)) == int(ex["frozen_saving_percent"])
+
+
+@pytest.mark.parametrize("n,a", [(1, 1), (2, 1), (6, 2), (7, 3), (8, 8), (13, 4), (64, 5), (66, 66)])
+def test_exactly_once_and_window_size(orc, n, a):
+    """Every operator is active in exactly one slot; W = ceil(n / a); the last slot may be short;
+    frozen set of slot k = operators of later slots (Algorithm 1, GenerateSchedule)."""
+    order = W.seeded_permutation(n, seed=n * 31 + a)
+    slots, window = orc.generate_schedule(order, a)
+    assert window == math.ceil(n / a)
+    assert orc.check_schedule(order, slots, window) == orc.OK
+    counts = [0] * n
+    for k in range(window):
+        active = [e for e in range(n) if slots[e] == k]
+        assert active and len(active) <= a
+        assert set(active) == set(order[k * a:(k + 1) * a])
+        frozen = {e for e in range(n) if slots[e] > k}
+        assert frozen == set(order[(k + 1) * a:])
+        for e in active:
+            counts[e] += 1
+    assert counts == [1] * n
+
+
+def test_check_schedule_rejects(orc):
+    assert orc.check_schedule([0, 1, 2], [0, 1, 2], 3) == orc.OK
+    assert orc.check_schedule([0, 1, 1], [0, 1, 2], 3) == orc.NOT_A_SCHEDULE   # not a permutation
+    assert orc.check_schedule([0, 1, 2], [0, 1, 3], 3) == orc.NOT_A_SCHEDULE   # slot outside window
+    assert orc.check_schedule([2, 1, 0], [0, 1, 2], 3) == orc.NOT_A_SCHEDULE   # order walks back in slots
+    assert orc.check_schedule([2, 1, 0], [2, 1, 0], 3) == orc.OK
+
+
+def test_find_window_size_hand_cases(orc):
+    """Algorithm 1, FindWindowSize, against hand-worked cases."""
+    for row in _read_fixture("algorithm1_cases.txt"):
+        lhs, rhs = row.split("->")
+        o, t, sc, sm, so, bw = lhs.split()
+        w_exp, a_exp = (int(x) for x in rhs.split())
+        w, a = orc.find_window_size(int(o), float(t), float(sc), float(sm), float(so), float(bw))
+        assert (w, a) == (w_exp, a_exp), row
+
+
+def test_find_window_size_is_smallest_fitting(orc):
+    """Property: the chosen O_Active is the largest count >= 2 whose snapshot fits (cost is
+    monotone in O_Active), unless nothing above the floor fits."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 80))
+        sc, sm, so = 2.0, 4.0, 8.0
+        bw = float(rng.uniform(0.5, 20))
+        t = float(rng.uniform(0.1, 12 * n / bw * 1.2))
+        w, a = orc.find_window_size(n, t, sc, sm, so, bw)
+        fits = lambda k: ((sm + so) * k + sc * (n - k)) / bw <= t
+        if n <= 2:
+            assert a == n and w == 1
+            continue
+        best = max([k for k in range(3, n + 1) if fits(k)], default=2)
+        assert a == best and w == math.ceil(n / a)
+
+
+def test_order_by_popularity(orc):
+    """Ascending popularity, ties keep ascending operator id (Sec. 3.5)."""
+    pop = [5.0, 1.0, 3.0, 1.0, 9.0, 3.0, 0.5]
+    assert orc.order_by_popularity(pop) == [6, 1, 3, 2, 5, 0, 4]
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        p = rng.integers(0, 6, size=int(rng.integers(1, 40))).astype(float)
+        got = orc.order_by_popularity(list(p))
+        assert got == sorted(range(len(p)), key=lambda e: (p[e], e))
+
+
+# ---------------------------------------------------------------------------------------
+# layout
+# ---------------------------------------------------------------------------------------
+def _ragged_workload(seed=3, n_ops=7, window=3):
+    rng = np.random.default_rng(seed)
+    tensors = []
+    for e in range(n_ops):
+        for _ in range(int(rng.integers(1, 4))):
+            tensors.append((e, int(rng.integers(1, 3000))))
+    slots = [int(rng.integers(0, window)) for _ in range(n_ops)]
+    slots[0], slots[1] = 0, window - 1
+    return W.Workload("ragged", tensors, slots, window)
+
+
+@pytest.mark.parametrize("align", [16, 64, 256, 4096])
+def test_layout_offsets_bruteforce(orc, align):
+    """Offsets against an independent O(n^2) sum; aligned, monotone, non-overlapping; closed-form
+    payload 12*sum(active) + 2*sum(frozen)."""
+    wl = _ragged_workload()
+    model = model_of(wl, align=align)
+    numel = [n for _, n in wl.tensors]
+    for k in range(wl.window):
+        segs, total = orc.layout(model, k)
+        for j, (kind, t, nbytes, off) in enumerate(segs):
+            width = 2 if kind == orc.COMPUTE else 4
+            assert nbytes == numel[t] * width
+            brute = -(-256 // align) * align + sum(-(-segs[i][2] // align) * align for i in range(j))
+            assert off == brute and off % align == 0
+            if j:
+                assert off >= segs[j - 1][3] + segs[j - 1][2]
+        end = segs[-1][3] + -(-segs[-1][2] // align) * align if segs else -(-256 // align) * align
+        assert total == end
+        assert sum(s[2] for s in segs) == wl.slot_payload_bytes(k)
+        # each (kind, tensor) at most once; active tensors carry all three FP32 kinds
+        assert len({(s[0], s[1]) for s in segs}) == len(segs)
+        for t, (op, _) in enumerate(wl.tensors):
+            kinds = sorted(s[0] for s in segs if s[1] == t)
+            if wl.slot_of_op[op] == k:
+                assert kinds == [orc.MASTER, orc.ADAM_M, orc.ADAM_V]
+            elif wl.slot_of_op[op] > k:
+                assert kinds == [orc.COMPUTE]
+            else:
+                assert kinds == []
+
+
+def test_window_bytes_closed_form(orc):
+    """Uniform operators, n/W per slot: each operator is stored once with 12 B/param, and slot k
+    also holds 2 B/param for the n - (k+1) n/W operators still waiting, n (W-1)/2 operator-slots in
+    all; so window payload / dense payload = 1 + (W-1)/12."""
+    for cfg, ratio in ((W.tiny_moe(), 1.25), (W.mixtral_layer(d_model=64, d_ff=224), 1 + 7 / 12)):
+        model = model_of(cfg)
+        tot = 0
+        for k in range(cfg.window):
+            segs, _ = orc.layout(model, k)
+            tot += sum(s[2] for s in segs)
+        assert tot == pytest.approx(12 * cfg.n_params * ratio, rel=1e-12)
+
+
+def test_config_shapes_match_stated_sizes():
+    """The benchmark configurations have the parameter counts their descriptions state."""
+    c0, c1, c2, c3 = W.tiny_moe(), W.mixtral_layer(), W.fine_grained_stack(), W.ep_rank_share()
+    assert c0.n_params == 8 * 524288 and c0.window == 4
+    assert c1.n_params == 8 * 176160768 and c1.window == 8
+    assert c2.n_ops == 264 and c2.n_params == 264 * 8650752 and c2.window == 16
+    assert c3.n_ops == 512 and c3.n_params == 512 * 25165824 and c3.window == 8
+    # c2: 4 routed experts per layer per slot, shared experts join the last slot
+    for k in range(16):
+        n_active = sum(1 for s in c2.slot_of_op if s == k)
+        assert n_active == (16 if k < 15 else 24)
+    assert c2.slot_payload_bytes(0) == 16 * 12 * 8650752 + 248 * 2 * 8650752
+    assert c3.slot_payload_bytes(0) == 64 * 12 * 25165824 + 448 * 2 * 25165824
+
+
+# ---------------------------------------------------------------------------------------
+# pack / unpack
+# ---------------------------------------------------------------------------------------
+def test_pack_bytes_by_definition(orc):
+    """Every packed byte is accounted for: header fields, segment bytes equal to the source
+    tensor's bytes, zero padding, nothing else."""
+    wl = _ragged_workload(seed=11)
+    model = model_of(wl, align=64)
+    st = state_of(W.random_bits_state(wl, seed=2))
+    src = {orc.MASTER: st.master, orc.ADAM_M: st.m, orc.ADAM_V: st.v, orc.COMPUTE: st.compute}
+    for k in range(wl.window):
+        packed = orc.pack(model, k, 1234 + k, st)
+        segs, total = orc.layout(model, k)
+        assert packed.size == total
+        covered = np.zeros(total, dtype=bool)
+        covered[:256] = True
+        assert packed[:8].tobytes() == b"MOEVSNAP"
+        assert int.from_bytes(packed[8:12].tobytes(), "little") == 1
+        assert int.from_bytes(packed[12:16].tobytes(), "little") == k
+        assert int.from_bytes(packed[16:24].tobytes(), "little") == orc.plan_hash(model)
+        assert int.from_bytes(packed[24:32].tobytes(), "little") == 1234 + k
+        assert int.from_bytes(packed[32:40].tobytes(), "little") == len(segs)
+        assert int.from_bytes(packed[40:48].tobytes(), "little") == total - 256
+        assert int.from_bytes(packed[48:52].tobytes(), "little") == 64
+        assert not packed[52:256].any()
+        for kind, t, nbytes, off in segs:
+            assert packed[off:off + nbytes].tobytes() == src[kind][t].tobytes()
+            covered[off:off + nbytes] = True
+        assert not packed[~covered].any()  # padding is zero
+
+
+def test_plan_hash_distinguishes(orc):
+    wl = _ragged_workload(seed=4)
+    base = orc.plan_hash(model_of(wl))
+    other = _ragged_workload(seed=4)
+    other.tensors[0] = (other.tensors[0][0], other.tensors[0][1] + 1)
+    assert orc.plan_hash(model_of(other)) != base
+    assert orc.plan_hash(model_of(wl, align=512)) != base
+    assert orc.plan_hash(model_of(wl, widths=(4, 4, 1))) != base
+    assert orc.plan_hash(model_of(wl)) == base
+
+
+@pytest.mark.parametrize("align", [16, 256])
+def test_pack_unpack_identity_and_sentinel(orc, align):
+    """pack then unpack restores exactly the slot's tensors and touches nothing else; the mask
+    marks the slot's operators active and later ones frozen."""
+    wl = _ragged_workload(seed=7, n_ops=9, window=4)
+    model = model_of(wl, align=align)
+    truth = state_of(W.random_bits_state(wl, seed=5))
+    for k in range(wl.window):
+        packed = orc.pack(model, k, 10 + k, truth)
+        target = orc.poisoned_like(truth)
+        before = target.clone()
+        mask = np.full(wl.n_ops, 7, dtype=np.uint8)
+        assert orc.unpack(model, k, packed, target, mask) == 10 + k
+        for t, (op, _) in enumerate(wl.tensors):
+            s = wl.slot_of_op[op]
+            if s == k:
+                for kind in ("master", "m", "v"):
+                    assert target.kinds()[kind][t].tobytes() == truth.kinds()[kind][t].tobytes()
+                # compute weights of a newly active operator are derived from the master weights
+                exp = orc.bf16_rne_array(truth.master[t])
+                assert np.array_equal(target.compute[t], exp)
+            elif s > k:
+                assert target.compute[t].tobytes() == truth.compute[t].tobytes()
+                for kind in ("master", "m", "v"):
+                    assert target.kinds()[kind][t].tobytes() == before.kinds()[kind][t].tobytes()
+            else:
+                for kind in ("master", "m", "v", "compute"):
+                    assert target.kinds()[kind][t].tobytes() == before.kinds()[kind][t].tobytes()
+        for e in range(wl.n_ops):
+            s = wl.slot_of_op[e]
+            assert mask[e] == (1 if s == k else 0 if s > k else 7)
+
+
+def test_unpack_refuses_foreign_snapshots(orc):
+    wl = _ragged_workload(seed=9)
+    model = model_of(wl)
+    st = state_of(W.random_bits_state(wl, seed=1))
+    packed = orc.pack(model, 1, 11, st)
+    mask = np.zeros(wl.n_ops, dtype=np.uint8)
+    with pytest.raises(orc.OracleError) as e:
+        orc.unpack(model, 0, packed, st, mask)          # wrong slot (and too short / other size)
+    assert e.value.code in (orc.BAD_SNAPSHOT, orc.TOO_SMALL)
+    bad = packed.copy()
+    bad[0] ^= 1
+    with pytest.raises(orc.OracleError) as e:
+        orc.unpack(model, 1, bad, st, mask)
+    assert e.value.code == orc.BAD_SNAPSHOT
+    other = model_of(wl, align=512)
+    with pytest.raises(orc.OracleError):
+        orc.unpack(other, 1, packed, st, mask)
+    with pytest.raises(orc.OracleError) as e:
+        orc.unpack(model, 1, packed[:-1].copy(), st, mask)
+    assert e.value.code == orc.TOO_SMALL
+
+
+def test_empty_and_single_slot_edges(orc):
+    """W = 1 (dense checkpoint: everyone active, no compute segments) and a slot with no active operator."""
+    wl = W.Workload("dense", [(0, 10), (1, 7)], [0, 0], 1)
+    model = model_of(wl, align=16)
+    segs, total = orc.layout(model, 0)
+    assert [s[0] for s in segs] == [0, 1, 2, 0, 1, 2]
+    assert total == 256 + 3 * 48 + 3 * 32
+    wl2 = W.Workload("gap", [(0, 10), (1, 7)], [0, 2], 3)
+    model2 = model_of(wl2, align=16)
+    segs, total = orc.layout(model2, 1)
+    assert [(s[0], s[1]) for s in segs] == [(orc.COMPUTE, 1)]
+    segs, total = orc.layout(model2, 2)
+    assert [(s[0], s[1]) for s in segs] == [(0, 1), (1, 1), (2, 1)]
