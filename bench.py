@@ -1,0 +1,307 @@
+#!/usr/bin/env python3
+"""bench.py -- throughput of the sparse-snapshot / sparse-to-dense hot path on one MI355X.
+
+One "step" is one pass of the whole HBM-resident hot path over one window of the workload:
+    for every slot k:  snapshot_pack(k)                       (Sec. 3.2)
+    for every slot i:  restore_unpack(i); convert_replay(t0+i+1)   (Sec. 3.3)
+with the state, the gradients and the packed snapshots resident in HBM.  `value` is the
+algorithmic HBM bytes of a step divided by its wall time.  The device-to-host drain is bound by
+the host link, not by HBM; it is measured right after the timed steps and reported in its own
+object (it never enters `value`).
+
+Prints ONE JSON line.  Default workload: configs[1] (Mixtral-8x7B-shaped MoE layer).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+METRIC = "snapshot pack/restore GB/s (% HBM peak) + convert_replay iters/s, 1 GPU"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="c1", choices=["c0", "c1", "c2", "c4"])
+    ap.add_argument("--no-drain", action="store_true", help="skip the host-link drain measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--overlap", action="store_true", help="also time the drain under a concurrent bf16 GEMM loop")
+    ap.add_argument("--copy-tile", type=int, default=0)
+    ap.add_argument("--adam-tile", type=int, default=0)
+    ap.add_argument("--copy-blocks", type=int, default=0)
+    ap.add_argument("--adam-blocks", type=int, default=0)
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------
+# algorithmic bytes (what the method itself must move; stated per unit in the design doc)
+# ---------------------------------------------------------------------------------------
+def pack_bytes(wl, k):
+    return 2 * wl.slot_payload_bytes(k)            # read every payload byte once, write it once
+
+
+def unpack_bytes(wl, k):
+    newly_active = sum(p for e, p in enumerate(wl.params_of_op()) if wl.slot_of_op[e] == k)
+    return 2 * wl.slot_payload_bytes(k) + 2 * newly_active   # + derived bf16 weights of the new operators
+
+
+def replay_bytes(wl, i):
+    return 30 * wl.active_params_at(i)             # read p, m, v, g (16 B), write p, m, v (12 B) + bf16 (2 B)
+
+
+def read_traffic(kernel, workload):
+    """HBM traffic per launch measured with rocprofv3 --pmc (profiles/hbm_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 4 and not line.startswith("#") and parts[0] == kernel and parts[1] == workload:
+            return float(parts[2]) + float(parts[3])
+    return None
+
+
+# ---------------------------------------------------------------------------------------
+def cpu_baseline(cfg_name, seed):
+    """The oracle, as it stands, on a bounded sample of the same workload (single thread)."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2412_15411_amd import workloads as W
+
+    oracle.build()
+    if cfg_name == "c1":
+        wl = W.mixtral_layer(d_ff=14336 // 8)
+        sample = "configs[1] with d_ff 1792 (1/8 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
+    elif cfg_name in ("c2", "c4"):
+        wl = W.fine_grained_stack(n_layers=1, n_routed=16, n_shared=2, per_slot=4, heavy_tail=cfg_name == "c4")
+        sample = "one layer of 16 routed + 2 shared experts at full expert size, W=4, whole window"
+    else:
+        wl = W.tiny_moe()
+        sample = "configs[0], whole window"
+
+    def np_of(t):
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    st = W.make_state(wl, seed=seed)
+    state = oracle.State(*[[np_of(t) for t in st[k]] for k in ("master", "m", "v", "compute")])
+    model = oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window)
+    hp = oracle.AdamHP(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
+    grads = [np_of(g) for g in W.make_grads(wl, wl.t0 + 1, seed=seed)]
+    snaps = [np.empty(oracle.layout(model, k)[1], dtype=np.uint8) for k in range(wl.window)]
+    for s in snaps:
+        s.fill(0)  # touch the pages before timing
+    total_bytes = 0
+    t_begin = time.perf_counter()
+    for k in range(wl.window):
+        oracle.pack(model, k, wl.t0 + k, state, out=snaps[k])
+        total_bytes += pack_bytes(wl, k)
+    t_pack = time.perf_counter()
+    mask = np.zeros(wl.n_ops, dtype=np.uint8)
+    t_unpack = t_replay = 0.0
+    for i in range(wl.window):
+        t0 = time.perf_counter()
+        oracle.unpack(model, i, snaps[i], state, mask)
+        t1 = time.perf_counter()
+        oracle.replay_step(model, hp, wl.t0 + i + 1, mask, grads, state)
+        t2 = time.perf_counter()
+        t_unpack += t1 - t0
+        t_replay += t2 - t1
+        total_bytes += unpack_bytes(wl, i) + replay_bytes(wl, i)
+    elapsed = time.perf_counter() - t_begin
+    return {
+        "value": round(total_bytes / elapsed / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": sample, "seconds": round(elapsed, 2),
+        "pack_GBs": round(sum(pack_bytes(wl, k) for k in range(wl.window)) / (t_pack - t_begin) / 1e9, 3),
+        "unpack_GBs": round(sum(unpack_bytes(wl, k) for k in range(wl.window)) / t_unpack / 1e9, 3),
+        "replay_GBs": round(sum(replay_bytes(wl, k) for k in range(wl.window)) / t_replay / 1e9, 3),
+        "replay_iters_per_s": round(wl.window / t_replay, 3),
+    }
+
+
+# ---------------------------------------------------------------------------------------
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (each expert-parallel rank snapshots and converts its own "
+              "experts independently; there is nothing to exchange). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2412_15411_amd import binding as B
+    from paper_2412_15411_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = W.CONFIGS[args.config]()
+    t_setup = time.time()
+    log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
+    st = W.make_state(wl, seed=args.seed, device=dev)
+    state = B.State(st["master"], st["m"], st["v"], st["compute"])
+    grads = {}
+    for i in range(wl.window):
+        grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev)
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+    for knob, val in ((B.TUNE_COPY_TILE_BYTES, args.copy_tile), (B.TUNE_ADAM_TILE_ELEMS, args.adam_tile),
+                      (B.TUNE_COPY_MAX_BLOCKS, args.copy_blocks), (B.TUNE_ADAM_MAX_BLOCKS, args.adam_blocks)):
+        if val:
+            B.moev_tune(plan, knob, val)
+    if args.nontemporal >= 0:
+        B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
+    packed = [torch.empty(B.ckpt_plan_packed_bytes(plan, k), dtype=torch.uint8, device=dev) for k in range(wl.window)]
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    B.ckpt_plan_upload(plan, stream)
+    torch.cuda.synchronize()
+    log(f"[bench] inputs resident in HBM after {time.time() - t_setup:.1f} s; "
+        f"{torch.cuda.memory_allocated() / 1e9:.1f} GB allocated")
+
+    timings = []  # (kind, algorithmic bytes, start event, end event)
+
+    def timed(kind, nbytes, fn, record):
+        if record:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            timings.append((kind, nbytes, e0, e1))
+        else:
+            fn()
+
+    def one_step(record):
+        for k in range(wl.window):
+            timed("pack", pack_bytes(wl, k),
+                  lambda: B.snapshot_pack(plan, k, wl.t0 + k, state, packed[k], stream=stream), record)
+        mask.zero_()  # on torch's current stream == `stream` inside the with-block below
+        for i in range(wl.window):
+            timed("unpack", unpack_bytes(wl, i),
+                  lambda: B.restore_unpack(plan, i, None, packed[i], state, mask, stream=stream), record)
+            timed("replay", replay_bytes(wl, i),
+                  lambda: B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay,
+                                           wl.t0 + i + 1, mask, grads[wl.t0 + i + 1], state, stream=stream), record)
+
+    step_bytes = sum(pack_bytes(wl, k) + unpack_bytes(wl, k) + replay_bytes(wl, k) for k in range(wl.window))
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            one_step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(True)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    B.ckpt_plan_device_status(plan, stream)
+    ms_per_step = elapsed / args.steps * 1e3
+    value = step_bytes / (elapsed / args.steps) / 1e9
+
+    per_kind = {}
+    for kind, nbytes, e0, e1 in timings:
+        d = per_kind.setdefault(kind, {"bytes": 0, "ms": 0.0, "launches": 0})
+        d["bytes"] += nbytes
+        d["ms"] += e0.elapsed_time(e1)
+        d["launches"] += 1
+    kernels = {}
+    for kind, d in per_kind.items():
+        gbs = d["bytes"] / (d["ms"] / 1e3) / 1e9
+        kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
+                         "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
+    dominant = max(per_kind, key=lambda k: per_kind[k]["ms"])
+    kname = {"pack": "k_pack", "unpack": "k_unpack", "replay": "k_adam"}[dominant]
+    roofline = {"bound": "hbm", "kernel": kname, "achieved": kernels[dominant]["GBs"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kernels[dominant]["frac_hbm_peak"],
+                "traffic": read_traffic(kname, args.config)}
+    replay_iters_per_s = per_kind["replay"]["launches"] / (per_kind["replay"]["ms"] / 1e3)
+
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config[1]}] {wl.name}", "n_ops": wl.n_ops, "n_params": wl.n_params,
+                   "window": wl.window, "step": "W x snapshot_pack + W x (restore_unpack + convert_replay), HBM-resident",
+                   "step_algorithmic_bytes": step_bytes},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "replay_iters_per_s": round(replay_iters_per_s, 2),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    # ---- drain: host link, measured outside the timed steps --------------------------------
+    if not args.no_drain:
+        k = 0
+        nbytes = B.ckpt_plan_packed_bytes(plan, k)
+        host = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+        side = torch.cuda.Stream()
+        B.snapshot_pack(plan, k, wl.t0, state, packed[k], stream=stream)
+        done = torch.cuda.Event()
+        done.record(stream)
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            B.snapshot_drain(plan, k, packed[k], host, side_stream=side, pack_done=done)
+            e1.record(side)
+            side.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        out["drain"] = {"bound": "host-link", "slot": k, "bytes": nbytes, "ms": round(best, 3),
+                        "GBs": round(nbytes / (best / 1e3) / 1e9, 2)}
+        ok = B.snapshot_peek(plan, k, host)["slot"] == k
+        out["drain"]["header_ok"] = bool(ok)
+        if args.overlap:
+            a = torch.randn(8192, 4096, dtype=torch.bfloat16, device=dev)
+            b = torch.randn(4096, 2048, dtype=torch.bfloat16, device=dev)
+            n_gemm = 2000
+
+            def gemm_loop():
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                with torch.cuda.stream(stream):
+                    e0.record(stream)
+                    for _ in range(n_gemm):
+                        torch.mm(a, b)
+                    e1.record(stream)
+                return e0, e1
+            g0, g1 = gemm_loop()
+            torch.cuda.synchronize()
+            alone_ms = g0.elapsed_time(g1)
+            g0, g1 = gemm_loop()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            B.snapshot_drain(plan, k, packed[k], host, side_stream=side)
+            e1.record(side)
+            torch.cuda.synchronize()
+            out["drain_under_gemm"] = {
+                "gemm": "bf16 [8192x4096]x[4096x2048] x %d on the main stream" % n_gemm,
+                "drain_GBs": round(nbytes / (e0.elapsed_time(e1) / 1e3) / 1e9, 2),
+                "gemm_ms_alone": round(alone_ms, 2), "gemm_ms_with_drain": round(g0.elapsed_time(g1), 2)}
+        del host
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.seed)
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

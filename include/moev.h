@@ -1,0 +1,247 @@
+/*
+ * moev.h -- C ABI of libmoev: sparse snapshot of MoE expert state and sparse-to-dense
+ * checkpoint conversion (MoEvement, arXiv 2412.15411) on one MI355X (gfx950).
+ *
+ * The five calls follow the paper's statement of the problem:
+ *   ckpt_plan       Sec. 3.5 / Algorithm 1: window size, operator order, per-slot active and
+ *                   frozen sets; plus this library's packed-snapshot layout for every slot.
+ *   snapshot_pack   Sec. 3.2: gather the slot's sparse snapshot (full FP32 state of the active
+ *                   operators, compute weights of the frozen ones) into one packed buffer.
+ *   snapshot_drain  Sec. 3.2 / Sec. 4: move the snapshot to pinned host memory on a side
+ *                   stream, overlapped with training.
+ *   restore_unpack  Sec. 3.3 (steps 1, 3, 5 of the walk-through): load one sparse snapshot,
+ *                   activate the operators whose FP32 state it carries.
+ *   convert_replay  Sec. 3.3 (steps 2, 4, 6): one replayed optimizer step on the active
+ *                   operators; frozen operators are skipped.
+ *
+ * Conventions
+ *   - Every call returns 0 (MOEV_OK) or a negative MOEV_E_* code; moev_last_error() gives
+ *     a thread-local message for the last failure.  No exception crosses the boundary.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device memory
+ *     of the GPU that was current when the plan was first used on the GPU.
+ *   - All data buffers are owned by the caller.  The library owns only the opaque plan and
+ *     its small device tables, released by ckpt_plan_free().
+ *   - GPU calls enqueue work on the given stream and return; they never synchronise the
+ *     device (the two ckpt_plan_device_* queries do, they exist for tests).
+ *   - Streams and events are passed as void* (hipStream_t / hipEvent_t); NULL stream = the
+ *     default stream.
+ *   - There is no CPU fallback: GPU calls fail with MOEV_E_HIP when no device is usable.
+ *
+ * Packed snapshot format (this library's definition; the paper copies per operator and
+ * defines none).  Little endian.
+ *   [256-byte header][segment 0][zero pad][segment 1][zero pad]...
+ *   header: +0 u64 magic "MOEVSNAP", +8 u32 version = 1, +12 u32 slot, +16 u64 plan hash,
+ *           +24 u64 iteration, +32 u64 segment count, +40 u64 payload bytes (all bytes after
+ *           the header), +48 u32 align, rest zero.
+ *   segments of slot k: walking the checkpoint order, for every operator active in slot k and
+ *           each of its tensors: master, Adam m, Adam v; then, walking the order again, for
+ *           every operator active in a later slot and each of its tensors: compute weights.
+ *   offsets: first segment at roundup(256, align); each next one roundup(nbytes, align)
+ *           further; padding bytes are zero.
+ *   plan hash: 64-bit FNV-1a over u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 element
+ *           widths (master, optimizer, compute), per tensor (u32 op, u64 numel), per operator
+ *           u32 slot, per position u32 order.
+ */
+#ifndef MOEV_H
+#define MOEV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MOEV_OK = 0,
+  MOEV_E_INVAL = -1,    /* bad argument (null, misaligned, not a schedule, ...) */
+  MOEV_E_NOMEM = -2,    /* host or device allocation failed */
+  MOEV_E_RANGE = -3,    /* slot >= window, buffer too small */
+  MOEV_E_MISMATCH = -4, /* snapshot header does not belong to this plan / slot */
+  MOEV_E_HIP = -5       /* a HIP runtime call failed; see moev_last_error() */
+};
+
+enum { MOEV_KIND_MASTER = 0, MOEV_KIND_ADAM_M = 1, MOEV_KIND_ADAM_V = 2, MOEV_KIND_COMPUTE = 3 };
+
+enum {
+  MOEV_EXPLICIT = 0, /* slot_of_op given by the caller */
+  MOEV_FIXED = 1,    /* GenerateSchedule of Algorithm 1 from `order` and `n_active` */
+  MOEV_AUTO = 2      /* FindWindowSize of Algorithm 1 from t_iter_s and host_link_Bps, then FIXED */
+};
+
+#define MOEV_HEADER_BYTES 256u
+
+typedef struct moev_plan moev_plan; /* opaque */
+
+/* one parameter tensor of operator `op`.  Tensors are listed grouped by operator, operators
+ * in ascending id starting at 0. */
+typedef struct {
+  uint32_t op;
+  uint64_t numel;
+} moev_tensor;
+
+typedef struct {
+  uint32_t n_ops, n_tensors;
+  const moev_tensor *tensors;  /* host, [n_tensors] */
+  int mode;                    /* MOEV_EXPLICIT / MOEV_FIXED / MOEV_AUTO */
+  uint32_t window;             /* EXPLICIT: W_sparse.  Ignored otherwise (derived). */
+  uint32_t n_active;           /* FIXED: operators checkpointed with full state per slot (O_Active) */
+  const uint32_t *order;       /* host, [n_ops]: O_Ordered, the checkpoint order (ascending popularity).
+                                  FIXED/AUTO: NULL = identity.  EXPLICIT: NULL = by (slot, id); if given,
+                                  slots must not decrease along it. */
+  const uint32_t *slot_of_op;  /* host, [n_ops]: EXPLICIT only */
+  double t_iter_s;             /* AUTO: T_Iter */
+  double host_link_Bps;        /* AUTO: B_PCIe, bytes per second */
+  uint32_t align;              /* segment alignment in the packed buffer: power of two >= 16; 0 = 256 */
+  uint8_t master_bytes;        /* element widths; 0 = defaults 4, 4, 2 */
+  uint8_t opt_bytes_each;
+  uint8_t compute_bytes;
+} moev_plan_cfg;
+
+typedef struct {
+  uint32_t kind;   /* MOEV_KIND_* */
+  uint32_t tensor;
+  uint64_t nbytes;
+  uint64_t dst_off;
+} moev_segment;
+
+/* dense training state: four host arrays [n_tensors] of device pointers.  Each tensor is
+ * contiguous and 16-byte aligned. */
+typedef struct {
+  void *const *master;
+  void *const *m;
+  void *const *v;
+  void *const *compute;
+} moev_state;
+
+/* Adam hyper-parameters and the global iteration number of the step to replay (all operators
+ * share it; it drives the bias corrections 1 - beta^step). */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  uint64_t step;
+} moev_adam;
+
+typedef struct {
+  uint64_t magic;
+  uint32_t version, slot;
+  uint64_t plan_hash, iter, n_segments, payload_bytes;
+  uint32_t align;
+} moev_header;
+
+/* launch knobs for moev_tune() */
+enum {
+  MOEV_TUNE_COPY_TILE_BYTES = 0, /* bytes of packed buffer one workgroup handles per step (multiple of 4096) */
+  MOEV_TUNE_COPY_MAX_BLOCKS = 1, /* cap on the pack/unpack grid (0 = 8 per compute unit); lower it to leave
+                                    compute units to concurrent kernels */
+  MOEV_TUNE_ADAM_TILE_ELEMS = 2, /* elements one workgroup handles per step (multiple of 1024) */
+  MOEV_TUNE_ADAM_MAX_BLOCKS = 3,
+  MOEV_TUNE_NONTEMPORAL = 4      /* 1 = streaming (nontemporal) loads and stores, 0 = default caching */
+};
+
+const char *moev_last_error(void);
+
+/* ---- plan (host only; needs no GPU) -------------------------------------------------
+ * Algorithm 1 / Sec. 3.5.  Builds slot(e) for every operator, validates that every operator
+ * is active in exactly one slot, and lays out the packed snapshot of every slot.  On success
+ * *out holds a new plan.  Errors: MOEV_E_INVAL, MOEV_E_NOMEM. */
+int ckpt_plan(const moev_plan_cfg *cfg, moev_plan **out);
+void ckpt_plan_free(moev_plan *plan);
+
+/* Algorithm 1 helpers, usable without a plan.  FindWindowSize with per-operator sizes in
+ * bytes; OrderOperators (ascending popularity, stable, ties by ascending id); the re-order
+ * trigger of Sec. 3.5 (returns 1 when the activation frequency changed by more than
+ * rel_change for at least min_fraction of the operators; the paper uses 0.10 and 0.25). */
+int moev_find_window_size(uint32_t n_ops, double t_iter_s, double compute_bytes_per_op,
+                          double master_bytes_per_op, double optim_bytes_per_op, double host_link_Bps,
+                          uint32_t *window, uint32_t *n_active);
+int moev_order_operators(uint32_t n_ops, const double *popularity, uint32_t *order);
+int moev_reorder_needed(uint32_t n_ops, const double *old_freq, const double *new_freq,
+                        double rel_change, double min_fraction);
+
+/* queries (host) */
+uint32_t ckpt_plan_window(const moev_plan *plan);
+uint32_t ckpt_plan_n_ops(const moev_plan *plan);
+uint32_t ckpt_plan_n_tensors(const moev_plan *plan);
+uint32_t ckpt_plan_n_active(const moev_plan *plan);            /* O_Active (0 for EXPLICIT) */
+uint64_t ckpt_plan_hash(const moev_plan *plan);
+int ckpt_plan_slot_of_op(const moev_plan *plan, uint32_t *out /* host [n_ops] */);
+int ckpt_plan_order(const moev_plan *plan, uint32_t *out /* host [n_ops] */);
+uint64_t ckpt_plan_packed_bytes(const moev_plan *plan, uint32_t slot); /* 0 if slot >= window */
+uint64_t ckpt_plan_max_packed_bytes(const moev_plan *plan);
+uint32_t ckpt_plan_n_segments(const moev_plan *plan, uint32_t slot);
+/* copies up to cap entries of the slot's segment table (host-computed offsets); returns the
+ * number of segments of the slot or a negative error */
+int64_t ckpt_plan_segments(const moev_plan *plan, uint32_t slot, moev_segment *out, uint64_t cap);
+/* parameters updated by replay iteration i of a conversion: operators with slot <= i */
+uint64_t ckpt_plan_active_params(const moev_plan *plan, uint32_t i);
+
+int moev_tune(moev_plan *plan, int knob, int64_t value);
+int64_t moev_tune_get(const moev_plan *plan, int knob);
+
+/* ---- device side of the plan ---------------------------------------------------------
+ * Uploads the segment tables and computes, ON THE DEVICE with wavefront prefix sums, the
+ * offset of every segment and the tile-to-segment map of every slot.  Called implicitly by
+ * the first GPU call; call it yourself to keep that cost out of the first snapshot.
+ * Enqueues on `stream`. */
+int ckpt_plan_upload(moev_plan *plan, void *stream);
+/* test hook: copy the device-computed layout of a slot back (synchronises `stream`).
+ * dst_off_out: host [n_segments]; tile_start_out: host [n_segments + 1] or NULL. */
+int ckpt_plan_device_layout(moev_plan *plan, uint32_t slot, uint64_t *dst_off_out,
+                            uint32_t *tile_start_out, uint64_t *packed_bytes_out, void *stream);
+/* device status word (synchronises `stream`): 0; MOEV_E_MISMATCH if a restore_unpack found a
+ * foreign header in a device-resident snapshot and skipped it; MOEV_E_INVAL if a
+ * convert_replay met an active operator with a null gradient pointer and skipped it.
+ * Reading clears it. */
+int ckpt_plan_device_status(moev_plan *plan, void *stream);
+
+/* ---- snapshot (Sec. 3.2) ---------------------------------------------------------------
+ * snapshot_pack: one gather kernel.  Copies master, m, v of every tensor of the operators
+ * active in `slot` and the compute weights of every tensor of the operators active in later
+ * slots from `state` into d_packed (device, 256-byte aligned, cap >= packed_bytes(slot)),
+ * writes the header (with `iter` = the iteration whose post-update state this is) and zero
+ * padding.  Errors: MOEV_E_INVAL (null / misaligned pointer), MOEV_E_RANGE, MOEV_E_HIP. */
+int snapshot_pack(moev_plan *plan, uint32_t slot, uint64_t iter, const moev_state *state,
+                  void *d_packed, size_t cap, void *stream);
+
+/* snapshot_drain: packed_bytes(slot) bytes from d_packed (device) to h_pinned (pinned host,
+ * cap >= packed_bytes(slot)) with one asynchronous copy on `side_stream`.  If pack_done is
+ * non-NULL the copy waits for that event (record it on the pack stream after snapshot_pack);
+ * if drained is non-NULL it is recorded after the copy.  The host buffer is complete once
+ * `drained` (or the side stream) has been synchronised. */
+int snapshot_drain(moev_plan *plan, uint32_t slot, const void *d_packed, void *h_pinned, size_t cap,
+                   void *side_stream, void *pack_done, void *drained);
+
+/* parse and validate a snapshot header that lies in HOST memory against the plan and slot.
+ * Returns MOEV_OK, MOEV_E_MISMATCH or MOEV_E_INVAL; *out (optional) receives the fields. */
+int snapshot_peek(const moev_plan *plan, uint32_t slot, const void *h_packed, moev_header *out);
+
+/* ---- conversion (Sec. 3.3) -------------------------------------------------------------
+ * restore_unpack: load the snapshot of `slot`.  If h_pinned is non-NULL its header is checked
+ * on the host (MOEV_E_MISMATCH on a foreign snapshot; nothing is enqueued then) and
+ * packed_bytes(slot) bytes are first copied host-to-device into d_packed on `stream`;
+ * otherwise d_packed must already hold the snapshot and the header is checked by the
+ * kernel, which skips a foreign snapshot and raises the device status word.  Then one
+ * scatter kernel writes every segment back into `state`, sets compute = bf16(master)
+ * (round to nearest even) for the tensors of the newly active operators (FP32-master /
+ * 2-byte-compute regime only), and updates d_active_mask (device, [n_ops] bytes): 1 for the
+ * operators active in `slot`, 0 for the operators of later slots, earlier ones untouched. */
+int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d_packed,
+                   const moev_state *state, uint8_t *d_active_mask, void *stream);
+
+/* convert_replay: one fused Adam step of iteration adam->step on every tensor whose operator
+ * has d_active_mask != 0, with gradients grads (host array [n_tensors] of device pointers to
+ * fp32 gradients; entries of frozen operators are not read and may be NULL):
+ *     m = beta1*m + (1-beta1)*g;  v = beta2*v + (1-beta2)*(g*g);
+ *     p = p - lr*weight_decay*p            (only if weight_decay != 0)
+ *     p = p - lr * ((m/bc1) / (sqrt(v/bc2) + eps)),   bc = 1 - beta^step
+ *     compute = bf16(p)
+ * all in FP32, every operation rounded separately (no fused multiply-add), division and
+ * square root correctly rounded.  Tensors of frozen operators are not touched.
+ * Requires element widths 4, 4, 2.  Errors: MOEV_E_INVAL, MOEV_E_HIP. */
+int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
+                   void *const *grads, const moev_state *state, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEV_H */

@@ -1,0 +1,674 @@
+// api.hip -- extern "C" boundary of libmoev (declared in include/moev.h): argument checks,
+// device tables of the plan, kernel launches, the side-stream drain.  No arithmetic of the
+// method happens on the host: every byte moved and every Adam update runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+#include "moev.h"
+#include "plan.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define MOEV_HIP(call)                                                                     \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return fail(MOEV_E_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+constexpr uint64_t kMagic = 0x50414e5356454f4dull;  // "MOEVSNAP" read as a little-endian u64
+constexpr int kRing = 8;
+
+struct StageSlot {
+  void* pinned = nullptr;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+
+}  // namespace
+
+struct moev_plan {
+  moev::HostPlan host;
+  std::mutex mu;
+
+  // launch knobs
+  int64_t copy_tile_bytes = 32768;
+  int64_t copy_max_blocks = 0;
+  int64_t adam_tile_elems = 8192;
+  int64_t adam_max_blocks = 0;
+  int64_t nontemporal = 1;
+
+  // device side
+  int device = -1;
+  int n_cu = 0;
+  bool uploaded = false;
+  bool broken = false;
+  void* pinned_tables = nullptr;  // staging of the static tables, kept until the plan is freed
+  char* d_tables = nullptr;       // one allocation holding every static table
+  moev::SegDesc* d_segs = nullptr;
+  uint64_t* d_dst_off = nullptr;
+  uint32_t* d_seg_tile_start = nullptr;     // per slot: n_segments + 1 entries
+  uint64_t* d_slot_total = nullptr;
+  uint64_t* d_numel = nullptr;
+  uint32_t* d_op_of_tensor = nullptr;
+  uint32_t* d_slot_of_op = nullptr;
+  uint32_t* d_tensor_tile_start = nullptr;  // n_tensors + 1
+  moev::ScanJob* d_jobs = nullptr;
+  uint32_t* d_status = nullptr;
+  void** d_state_ptrs = nullptr;            // [4 * n_tensors]
+  void** d_grad_ptrs = nullptr;             // [n_tensors]
+  std::vector<void*> state_cache, grad_cache;
+  bool state_valid = false, grad_valid = false;
+  StageSlot ring[kRing];
+  int ring_next = 0;
+  std::vector<uint32_t> slot_tiles;         // host-side tile counts (grid sizing only)
+  uint32_t tensor_tiles = 0;
+
+  ~moev_plan() {
+    if (device >= 0) {
+      int cur = -1;
+      if (hipGetDevice(&cur) == hipSuccess && cur != device) (void)hipSetDevice(device);
+      for (auto& r : ring) {
+        if (r.done) {
+          (void)hipEventSynchronize(r.done);
+          (void)hipEventDestroy(r.done);
+        }
+        if (r.pinned) (void)hipHostFree(r.pinned);
+      }
+      if (d_tables) (void)hipFree(d_tables);
+      if (d_state_ptrs) (void)hipFree(d_state_ptrs);
+      if (d_grad_ptrs) (void)hipFree(d_grad_ptrs);
+      if (pinned_tables) (void)hipHostFree(pinned_tables);
+      if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+    }
+  }
+};
+
+namespace {
+
+using moev::round_up;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint32_t tiles_of(uint64_t padded, uint64_t tile) { return static_cast<uint32_t>((padded + tile - 1) / tile); }
+
+void compute_host_tiles(moev_plan* pl) {
+  const auto& h = pl->host;
+  pl->slot_tiles.assign(h.window, 0);
+  for (uint32_t k = 0; k < h.window; ++k) {
+    uint64_t n = 0;
+    for (uint32_t j = 0; j < h.slots[k].n_segments; ++j)
+      n += tiles_of(round_up(h.segments[h.slots[k].first_segment + j].nbytes, h.align), pl->copy_tile_bytes);
+    pl->slot_tiles[k] = static_cast<uint32_t>(n);
+  }
+  uint64_t n = 0;
+  for (const auto& t : h.tensors) n += tiles_of(t.numel, pl->adam_tile_elems);
+  pl->tensor_tiles = static_cast<uint32_t>(n);
+}
+
+// First use on the GPU: allocates the device tables and fills their pinned mirror.
+int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
+  const auto& h = pl->host;
+  hipDeviceProp_t prop;
+  MOEV_HIP(hipGetDeviceProperties(&prop, dev));
+  pl->n_cu = prop.multiProcessorCount;
+  const size_t n_seg = h.segments.size();
+  // carve one device allocation (and a pinned mirror for the inputs) into the tables
+  size_t off = 0;
+  auto carve = [&](size_t bytes) {
+    size_t at = off;
+    off = (off + bytes + 255) & ~size_t(255);
+    return at;
+  };
+  const size_t o_segs = carve(n_seg * sizeof(moev::SegDesc));
+  const size_t o_numel = carve(h.n_tensors * sizeof(uint64_t));
+  const size_t o_opt = carve(h.n_tensors * sizeof(uint32_t));
+  const size_t o_slot = carve(h.n_ops * sizeof(uint32_t));
+  const size_t o_jobs = carve((h.window + 1) * sizeof(moev::ScanJob));
+  const size_t input_bytes = off;
+  const size_t o_dst = carve(n_seg * sizeof(uint64_t));
+  const size_t o_tile = carve((n_seg + h.window) * sizeof(uint32_t));
+  const size_t o_total = carve(h.window * sizeof(uint64_t));
+  const size_t o_ttile = carve((h.n_tensors + 1) * sizeof(uint32_t));
+  const size_t o_status = carve(sizeof(uint32_t));
+  pl->device = dev;  // from here on the destructor releases whatever was allocated
+  MOEV_HIP(hipMalloc(reinterpret_cast<void**>(&pl->d_tables), off));
+  MOEV_HIP(hipHostMalloc(&pl->pinned_tables, input_bytes, hipHostMallocDefault));
+  MOEV_HIP(hipMalloc(reinterpret_cast<void**>(&pl->d_state_ptrs), 4ull * h.n_tensors * sizeof(void*)));
+  MOEV_HIP(hipMalloc(reinterpret_cast<void**>(&pl->d_grad_ptrs), 1ull * h.n_tensors * sizeof(void*)));
+  for (auto& r : pl->ring) {
+    MOEV_HIP(hipHostMalloc(&r.pinned, 4ull * h.n_tensors * sizeof(void*), hipHostMallocDefault));
+    MOEV_HIP(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
+  }
+  char* d = pl->d_tables;
+  pl->d_segs = reinterpret_cast<moev::SegDesc*>(d + o_segs);
+  pl->d_numel = reinterpret_cast<uint64_t*>(d + o_numel);
+  pl->d_op_of_tensor = reinterpret_cast<uint32_t*>(d + o_opt);
+  pl->d_slot_of_op = reinterpret_cast<uint32_t*>(d + o_slot);
+  pl->d_jobs = reinterpret_cast<moev::ScanJob*>(d + o_jobs);
+  pl->d_dst_off = reinterpret_cast<uint64_t*>(d + o_dst);
+  pl->d_seg_tile_start = reinterpret_cast<uint32_t*>(d + o_tile);
+  pl->d_slot_total = reinterpret_cast<uint64_t*>(d + o_total);
+  pl->d_tensor_tile_start = reinterpret_cast<uint32_t*>(d + o_ttile);
+  pl->d_status = reinterpret_cast<uint32_t*>(d + o_status);
+
+  char* m = static_cast<char*>(pl->pinned_tables);
+  std::memset(m, 0, input_bytes);
+  auto* segs = reinterpret_cast<moev::SegDesc*>(m + o_segs);
+  for (size_t j = 0; j < n_seg; ++j) segs[j] = moev::SegDesc{h.segments[j].tensor, h.segments[j].kind, h.segments[j].nbytes};
+  auto* numel = reinterpret_cast<uint64_t*>(m + o_numel);
+  auto* opt = reinterpret_cast<uint32_t*>(m + o_opt);
+  for (uint32_t t = 0; t < h.n_tensors; ++t) {
+    numel[t] = h.tensors[t].numel;
+    opt[t] = h.tensors[t].op;
+  }
+  std::memcpy(m + o_slot, h.slot_of_op.data(), h.n_ops * sizeof(uint32_t));
+  MOEV_HIP(hipMemsetAsync(pl->d_status, 0, sizeof(uint32_t), s));
+  return MOEV_OK;
+}
+
+// Uploads the static tables and runs the on-device layout scan.  Caller holds pl->mu.
+int upload_locked(moev_plan* pl, hipStream_t s) {
+  const auto& h = pl->host;
+  if (pl->broken) return fail(MOEV_E_HIP, "the plan's device side could not be set up earlier; create a new plan");
+  int dev = -1;
+  MOEV_HIP(hipGetDevice(&dev));
+  if (pl->device >= 0 && pl->device != dev)
+    return fail(MOEV_E_INVAL, "plan lives on device %d but device %d is current", pl->device, dev);
+  if (pl->uploaded) return MOEV_OK;
+
+  if (pl->device < 0) {
+    int rc = allocate_device_side(pl, dev, s);
+    if (rc != MOEV_OK) {
+      pl->broken = true;
+      return rc;
+    }
+  }
+
+  // (re)build the scan jobs: they depend on the tile sizes, which moev_tune() may change
+  const size_t jobs_at = reinterpret_cast<char*>(pl->d_jobs) - pl->d_tables;
+  auto* jobs = reinterpret_cast<moev::ScanJob*>(static_cast<char*>(pl->pinned_tables) + jobs_at);
+  for (uint32_t k = 0; k < h.window; ++k) {
+    const uint32_t first = h.slots[k].first_segment;
+    jobs[k] = moev::ScanJob{&pl->d_segs[first].nbytes,
+                            pl->d_dst_off + first,
+                            pl->d_seg_tile_start + first + k,
+                            pl->d_slot_total + k,
+                            round_up(MOEV_HEADER_BYTES, h.align),
+                            h.align,
+                            static_cast<uint64_t>(pl->copy_tile_bytes),
+                            h.slots[k].n_segments,
+                            static_cast<uint32_t>(sizeof(moev::SegDesc) / sizeof(uint64_t))};
+  }
+  jobs[h.window] = moev::ScanJob{pl->d_numel, nullptr, pl->d_tensor_tile_start, nullptr, 0, 1,
+                                 static_cast<uint64_t>(pl->adam_tile_elems), h.n_tensors, 1};
+  const size_t input_bytes = jobs_at + (h.window + 1) * sizeof(moev::ScanJob);
+  MOEV_HIP(hipMemcpyAsync(pl->d_tables, pl->pinned_tables, input_bytes, hipMemcpyHostToDevice, s));
+  MOEV_HIP(moev::launch_layout_scan(pl->d_jobs, h.window + 1, s));
+  compute_host_tiles(pl);
+  pl->uploaded = true;
+  return MOEV_OK;
+}
+
+// Makes the device copy of a pointer table current.  Unchanged tables cost one memcmp.
+int sync_ptr_table(moev_plan* pl, std::vector<void*>& cache, bool& valid, void** d_table,
+                   const std::vector<void*>& wanted, hipStream_t s) {
+  if (valid && cache == wanted) return MOEV_OK;
+  StageSlot& slot = pl->ring[pl->ring_next];
+  pl->ring_next = (pl->ring_next + 1) % kRing;
+  if (slot.in_flight) MOEV_HIP(hipEventSynchronize(slot.done));
+  std::memcpy(slot.pinned, wanted.data(), wanted.size() * sizeof(void*));
+  MOEV_HIP(hipMemcpyAsync(d_table, slot.pinned, wanted.size() * sizeof(void*), hipMemcpyHostToDevice, s));
+  MOEV_HIP(hipEventRecord(slot.done, s));
+  slot.in_flight = true;
+  cache = wanted;
+  valid = true;
+  return MOEV_OK;
+}
+
+int check_state(const moev_plan* pl, const moev_state* st, const char* who) {
+  if (!st || !st->master || !st->m || !st->v || !st->compute)
+    return fail(MOEV_E_INVAL, "%s: state and its four pointer arrays must be non-null", who);
+  (void)pl;
+  return MOEV_OK;
+}
+
+int bind_state(moev_plan* pl, const moev_state* st, hipStream_t s) {
+  const uint32_t n = pl->host.n_tensors;
+  std::vector<void*> wanted(4ull * n);
+  for (uint32_t t = 0; t < n; ++t) {
+    wanted[t] = st->master[t];
+    wanted[1ull * n + t] = st->m[t];
+    wanted[2ull * n + t] = st->v[t];
+    wanted[3ull * n + t] = st->compute[t];
+  }
+  return sync_ptr_table(pl, pl->state_cache, pl->state_valid, pl->d_state_ptrs, wanted, s);
+}
+
+uint32_t grid_for(const moev_plan* pl, uint32_t tiles, int64_t cap) {
+  uint64_t limit = cap > 0 ? static_cast<uint64_t>(cap) : 8ull * static_cast<uint64_t>(pl->n_cu > 0 ? pl->n_cu : 256);
+  uint64_t g = tiles < limit ? tiles : limit;
+  return static_cast<uint32_t>(g ? g : 1);
+}
+
+void fill_header(const moev_plan* pl, uint32_t slot, uint64_t iter, uint64_t out[7]) {
+  const auto& h = pl->host;
+  out[0] = kMagic;
+  out[1] = 1ull | (static_cast<uint64_t>(slot) << 32);
+  out[2] = h.hash;
+  out[3] = iter;
+  out[4] = h.slots[slot].n_segments;
+  out[5] = h.slots[slot].packed_bytes - MOEV_HEADER_BYTES;
+  out[6] = h.align;
+}
+
+moev::CopyArgs copy_args(const moev_plan* pl, uint32_t slot, uint64_t iter, void* d_packed) {
+  const auto& h = pl->host;
+  const uint32_t first = h.slots[slot].first_segment;
+  moev::CopyArgs a{};
+  a.segs = pl->d_segs + first;
+  a.dst_off = pl->d_dst_off + first;
+  a.tile_start = pl->d_seg_tile_start + first + slot;
+  a.ptrs = pl->d_state_ptrs;
+  a.packed = static_cast<uint8_t*>(d_packed);
+  fill_header(pl, slot, iter, a.header);
+  a.n_seg = h.slots[slot].n_segments;
+  a.n_tensors = h.n_tensors;
+  a.tile_bytes = static_cast<uint32_t>(pl->copy_tile_bytes);
+  a.align = h.align;
+  a.lds_entries = a.n_seg + 1 <= moev::kMaxLdsEntries ? a.n_seg + 1 : 0;
+  a.slot = slot;
+  a.n_ops = h.n_ops;
+  a.slot_of_op = pl->d_slot_of_op;
+  a.status = pl->d_status;
+  return a;
+}
+
+// every pointer the slot's segments touch must be present and 16-byte aligned
+int check_slot_pointers(const moev_plan* pl, uint32_t slot, const moev_state* st, bool need_compute_of_active,
+                        const char* who) {
+  const auto& h = pl->host;
+  void* const* table[4] = {st->master, st->m, st->v, st->compute};
+  for (uint32_t j = 0; j < h.slots[slot].n_segments; ++j) {
+    const moev_segment& sg = h.segments[h.slots[slot].first_segment + j];
+    const void* p = table[sg.kind][sg.tensor];
+    if (sg.nbytes == 0) continue;  // an empty tensor is never dereferenced
+    if (!p || !aligned16(p))
+      return fail(MOEV_E_INVAL, "%s: tensor %u kind %u pointer is null or not 16-byte aligned", who, sg.tensor, sg.kind);
+    if (need_compute_of_active && sg.kind == MOEV_KIND_MASTER) {
+      const void* c = st->compute[sg.tensor];
+      if (!c || !aligned16(c))
+        return fail(MOEV_E_INVAL, "%s: compute pointer of tensor %u is null or not 16-byte aligned", who, sg.tensor);
+    }
+  }
+  return MOEV_OK;
+}
+
+}  // namespace
+
+// =====================================================================================
+extern "C" {
+
+const char* moev_last_error(void) { return g_last_error.c_str(); }
+
+int ckpt_plan(const moev_plan_cfg* cfg, moev_plan** out) {
+  if (!cfg || !out) return fail(MOEV_E_INVAL, "ckpt_plan: null argument");
+  *out = nullptr;
+  moev_plan* pl = new (std::nothrow) moev_plan();
+  if (!pl) return fail(MOEV_E_NOMEM, "ckpt_plan: out of host memory");
+  std::string err;
+  int rc;
+  try {
+    rc = moev::build_plan(*cfg, pl->host, err);
+  } catch (const std::bad_alloc&) {
+    delete pl;
+    return fail(MOEV_E_NOMEM, "ckpt_plan: out of host memory");
+  }
+  if (rc != MOEV_OK) {
+    delete pl;
+    return fail(rc, "%s", err.c_str());
+  }
+  // tile counts must fit 31 bits at the smallest tile size the knobs allow
+  for (const auto& s : pl->host.slots)
+    if (s.packed_bytes / 4096 + s.n_segments >= (1ull << 31)) {
+      delete pl;
+      return fail(MOEV_E_INVAL, "ckpt_plan: slot too large");
+    }
+  compute_host_tiles(pl);
+  *out = pl;
+  return MOEV_OK;
+}
+
+void ckpt_plan_free(moev_plan* plan) { delete plan; }
+
+int moev_find_window_size(uint32_t n_ops, double t_iter_s, double compute_bytes_per_op, double master_bytes_per_op,
+                          double optim_bytes_per_op, double host_link_Bps, uint32_t* window, uint32_t* n_active) {
+  int rc = moev::find_window_size(n_ops, t_iter_s, compute_bytes_per_op, master_bytes_per_op, optim_bytes_per_op,
+                                  host_link_Bps, window, n_active);
+  return rc == MOEV_OK ? rc : fail(rc, "moev_find_window_size: bad argument");
+}
+
+int moev_order_operators(uint32_t n_ops, const double* popularity, uint32_t* order) {
+  if (!popularity || !order) return fail(MOEV_E_INVAL, "moev_order_operators: null argument");
+  for (uint32_t e = 0; e < n_ops; ++e)
+    if (std::isnan(popularity[e])) return fail(MOEV_E_INVAL, "moev_order_operators: popularity %u is NaN", e);
+  moev::order_operators(n_ops, popularity, order);
+  return MOEV_OK;
+}
+
+// Sec. 3.5: operators are re-ordered when the activation frequency changed by more than
+// rel_change (relative to the old frequency) for at least min_fraction of the operators.
+int moev_reorder_needed(uint32_t n_ops, const double* old_freq, const double* new_freq, double rel_change,
+                        double min_fraction) {
+  if (!old_freq || !new_freq || n_ops == 0) return fail(MOEV_E_INVAL, "moev_reorder_needed: bad argument");
+  uint32_t moved = 0;
+  for (uint32_t e = 0; e < n_ops; ++e) {
+    const double base = std::fabs(old_freq[e]);
+    const double delta = std::fabs(new_freq[e] - old_freq[e]);
+    if (base > 0 ? delta > rel_change * base : delta > 0) ++moved;
+  }
+  return static_cast<double>(moved) >= min_fraction * static_cast<double>(n_ops) ? 1 : 0;
+}
+
+uint32_t ckpt_plan_window(const moev_plan* p) { return p ? p->host.window : 0; }
+uint32_t ckpt_plan_n_ops(const moev_plan* p) { return p ? p->host.n_ops : 0; }
+uint32_t ckpt_plan_n_tensors(const moev_plan* p) { return p ? p->host.n_tensors : 0; }
+uint32_t ckpt_plan_n_active(const moev_plan* p) { return p ? p->host.n_active : 0; }
+uint64_t ckpt_plan_hash(const moev_plan* p) { return p ? p->host.hash : 0; }
+
+int ckpt_plan_slot_of_op(const moev_plan* p, uint32_t* out) {
+  if (!p || !out) return fail(MOEV_E_INVAL, "ckpt_plan_slot_of_op: null argument");
+  std::memcpy(out, p->host.slot_of_op.data(), p->host.n_ops * sizeof(uint32_t));
+  return MOEV_OK;
+}
+
+int ckpt_plan_order(const moev_plan* p, uint32_t* out) {
+  if (!p || !out) return fail(MOEV_E_INVAL, "ckpt_plan_order: null argument");
+  std::memcpy(out, p->host.order.data(), p->host.n_ops * sizeof(uint32_t));
+  return MOEV_OK;
+}
+
+uint64_t ckpt_plan_packed_bytes(const moev_plan* p, uint32_t slot) {
+  return (p && slot < p->host.window) ? p->host.slots[slot].packed_bytes : 0;
+}
+
+uint64_t ckpt_plan_max_packed_bytes(const moev_plan* p) {
+  uint64_t m = 0;
+  if (p)
+    for (const auto& s : p->host.slots) m = s.packed_bytes > m ? s.packed_bytes : m;
+  return m;
+}
+
+uint32_t ckpt_plan_n_segments(const moev_plan* p, uint32_t slot) {
+  return (p && slot < p->host.window) ? p->host.slots[slot].n_segments : 0;
+}
+
+int64_t ckpt_plan_segments(const moev_plan* p, uint32_t slot, moev_segment* out, uint64_t cap) {
+  if (!p) return fail(MOEV_E_INVAL, "ckpt_plan_segments: null plan");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "ckpt_plan_segments: slot %u outside window %u", slot, p->host.window);
+  const auto& s = p->host.slots[slot];
+  if (out)
+    for (uint32_t j = 0; j < s.n_segments && j < cap; ++j) out[j] = p->host.segments[s.first_segment + j];
+  return s.n_segments;
+}
+
+uint64_t ckpt_plan_active_params(const moev_plan* p, uint32_t i) {
+  if (!p) return 0;
+  uint64_t n = 0;
+  for (const auto& t : p->host.tensors)
+    if (p->host.slot_of_op[t.op] <= i) n += t.numel;
+  return n;
+}
+
+int moev_tune(moev_plan* p, int knob, int64_t value) {
+  if (!p) return fail(MOEV_E_INVAL, "moev_tune: null plan");
+  std::lock_guard<std::mutex> lock(p->mu);
+  switch (knob) {
+    case MOEV_TUNE_COPY_TILE_BYTES:
+      if (value < 4096 || value % 4096 || value > (1 << 26)) return fail(MOEV_E_INVAL, "copy tile must be a multiple of 4096 in [4096, 64 MiB]");
+      p->copy_tile_bytes = value;
+      p->uploaded = false;  // tile tables are rebuilt by the next GPU call
+      break;
+    case MOEV_TUNE_ADAM_TILE_ELEMS:
+      if (value < 1024 || value % 1024 || value > (1 << 24)) return fail(MOEV_E_INVAL, "adam tile must be a multiple of 1024 in [1024, 16 Mi]");
+      p->adam_tile_elems = value;
+      p->uploaded = false;
+      break;
+    case MOEV_TUNE_COPY_MAX_BLOCKS:
+      if (value < 0 || value > (1 << 20)) return fail(MOEV_E_INVAL, "block cap out of range");
+      p->copy_max_blocks = value;
+      break;
+    case MOEV_TUNE_ADAM_MAX_BLOCKS:
+      if (value < 0 || value > (1 << 20)) return fail(MOEV_E_INVAL, "block cap out of range");
+      p->adam_max_blocks = value;
+      break;
+    case MOEV_TUNE_NONTEMPORAL:
+      p->nontemporal = value ? 1 : 0;
+      break;
+    default:
+      return fail(MOEV_E_INVAL, "moev_tune: unknown knob %d", knob);
+  }
+  compute_host_tiles(p);
+  return MOEV_OK;
+}
+
+int64_t moev_tune_get(const moev_plan* p, int knob) {
+  if (!p) return -1;
+  switch (knob) {
+    case MOEV_TUNE_COPY_TILE_BYTES: return p->copy_tile_bytes;
+    case MOEV_TUNE_COPY_MAX_BLOCKS: return p->copy_max_blocks;
+    case MOEV_TUNE_ADAM_TILE_ELEMS: return p->adam_tile_elems;
+    case MOEV_TUNE_ADAM_MAX_BLOCKS: return p->adam_max_blocks;
+    case MOEV_TUNE_NONTEMPORAL: return p->nontemporal;
+    default: return -1;
+  }
+}
+
+int ckpt_plan_upload(moev_plan* p, void* stream) {
+  if (!p) return fail(MOEV_E_INVAL, "ckpt_plan_upload: null plan");
+  std::lock_guard<std::mutex> lock(p->mu);
+  return upload_locked(p, static_cast<hipStream_t>(stream));
+}
+
+int ckpt_plan_device_layout(moev_plan* p, uint32_t slot, uint64_t* dst_off_out, uint32_t* tile_start_out,
+                            uint64_t* packed_bytes_out, void* stream) {
+  if (!p) return fail(MOEV_E_INVAL, "ckpt_plan_device_layout: null plan");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "ckpt_plan_device_layout: slot outside window");
+  std::lock_guard<std::mutex> lock(p->mu);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  const auto& sl = p->host.slots[slot];
+  if (dst_off_out && sl.n_segments)
+    MOEV_HIP(hipMemcpyAsync(dst_off_out, p->d_dst_off + sl.first_segment, sl.n_segments * sizeof(uint64_t),
+                            hipMemcpyDeviceToHost, s));
+  if (tile_start_out)
+    MOEV_HIP(hipMemcpyAsync(tile_start_out, p->d_seg_tile_start + sl.first_segment + slot,
+                            (sl.n_segments + 1) * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  if (packed_bytes_out)
+    MOEV_HIP(hipMemcpyAsync(packed_bytes_out, p->d_slot_total + slot, sizeof(uint64_t), hipMemcpyDeviceToHost, s));
+  MOEV_HIP(hipStreamSynchronize(s));
+  return MOEV_OK;
+}
+
+int ckpt_plan_device_status(moev_plan* p, void* stream) {
+  if (!p) return fail(MOEV_E_INVAL, "ckpt_plan_device_status: null plan");
+  std::lock_guard<std::mutex> lock(p->mu);
+  if (!p->uploaded && p->device < 0) return MOEV_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint32_t status = 0;
+  MOEV_HIP(hipMemcpyAsync(&status, p->d_status, sizeof(status), hipMemcpyDeviceToHost, s));
+  MOEV_HIP(hipStreamSynchronize(s));
+  if (status) {
+    MOEV_HIP(hipMemsetAsync(p->d_status, 0, sizeof(uint32_t), s));
+    MOEV_HIP(hipStreamSynchronize(s));
+    if (status == 2u) return fail(MOEV_E_INVAL, "convert_replay skipped an active operator whose gradient pointer was null");
+    return fail(MOEV_E_MISMATCH, "a device-resident snapshot was refused by restore_unpack (foreign header)");
+  }
+  return MOEV_OK;
+}
+
+int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* state, void* d_packed, size_t cap,
+                  void* stream) {
+  if (!p || !d_packed) return fail(MOEV_E_INVAL, "snapshot_pack: null argument");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "snapshot_pack: slot %u outside window %u", slot, p->host.window);
+  if (cap < p->host.slots[slot].packed_bytes)
+    return fail(MOEV_E_RANGE, "snapshot_pack: buffer of %zu bytes, slot needs %llu", cap,
+                static_cast<unsigned long long>(p->host.slots[slot].packed_bytes));
+  if (reinterpret_cast<uintptr_t>(d_packed) & 255u) return fail(MOEV_E_INVAL, "snapshot_pack: d_packed must be 256-byte aligned");
+  int rc = check_state(p, state, "snapshot_pack");
+  if (rc != MOEV_OK) return rc;
+  rc = check_slot_pointers(p, slot, state, false, "snapshot_pack");
+  if (rc != MOEV_OK) return rc;
+  std::lock_guard<std::mutex> lock(p->mu);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  const moev::CopyArgs a = copy_args(p, slot, iter, d_packed);
+  MOEV_HIP(moev::launch_pack(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  return MOEV_OK;
+}
+
+int snapshot_drain(moev_plan* p, uint32_t slot, const void* d_packed, void* h_pinned, size_t cap, void* side_stream,
+                   void* pack_done, void* drained) {
+  if (!p || !d_packed || !h_pinned) return fail(MOEV_E_INVAL, "snapshot_drain: null argument");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "snapshot_drain: slot %u outside window %u", slot, p->host.window);
+  const uint64_t nbytes = p->host.slots[slot].packed_bytes;
+  if (cap < nbytes) return fail(MOEV_E_RANGE, "snapshot_drain: host buffer too small");
+  hipStream_t s = static_cast<hipStream_t>(side_stream);
+  if (pack_done) MOEV_HIP(hipStreamWaitEvent(s, static_cast<hipEvent_t>(pack_done), 0));
+  MOEV_HIP(hipMemcpyAsync(h_pinned, d_packed, nbytes, hipMemcpyDeviceToHost, s));
+  if (drained) MOEV_HIP(hipEventRecord(static_cast<hipEvent_t>(drained), s));
+  return MOEV_OK;
+}
+
+int snapshot_peek(const moev_plan* p, uint32_t slot, const void* h_packed, moev_header* out) {
+  if (!p || !h_packed) return fail(MOEV_E_INVAL, "snapshot_peek: null argument");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "snapshot_peek: slot outside window");
+  uint64_t w[7];
+  std::memcpy(w, h_packed, sizeof(w));
+  moev_header hd;
+  hd.magic = w[0];
+  hd.version = static_cast<uint32_t>(w[1]);
+  hd.slot = static_cast<uint32_t>(w[1] >> 32);
+  hd.plan_hash = w[2];
+  hd.iter = w[3];
+  hd.n_segments = w[4];
+  hd.payload_bytes = w[5];
+  hd.align = static_cast<uint32_t>(w[6]);
+  if (out) *out = hd;
+  uint64_t want[7];
+  fill_header(p, slot, hd.iter, want);
+  if (std::memcmp(w, want, sizeof(w)) != 0)
+    return fail(MOEV_E_MISMATCH, "snapshot header does not match plan %016llx slot %u",
+                static_cast<unsigned long long>(p->host.hash), slot);
+  return MOEV_OK;
+}
+
+int restore_unpack(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_state* state,
+                   uint8_t* d_active_mask, void* stream) {
+  if (!p || !d_packed) return fail(MOEV_E_INVAL, "restore_unpack: null argument");
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "restore_unpack: slot %u outside window %u", slot, p->host.window);
+  if (reinterpret_cast<uintptr_t>(d_packed) & 255u) return fail(MOEV_E_INVAL, "restore_unpack: d_packed must be 256-byte aligned");
+  int rc = check_state(p, state, "restore_unpack");
+  if (rc != MOEV_OK) return rc;
+  const auto& h = p->host;
+  const bool derive = h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2;
+  rc = check_slot_pointers(p, slot, state, derive, "restore_unpack");
+  if (rc != MOEV_OK) return rc;
+  if (h_pinned) {
+    rc = snapshot_peek(p, slot, h_pinned, nullptr);
+    if (rc != MOEV_OK) return rc;
+  }
+  std::lock_guard<std::mutex> lock(p->mu);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  if (h_pinned)
+    MOEV_HIP(hipMemcpyAsync(d_packed, h_pinned, h.slots[slot].packed_bytes, hipMemcpyHostToDevice, s));
+  moev::CopyArgs a = copy_args(p, slot, 0, d_packed);
+  a.mask = d_active_mask;
+  a.derive_compute = derive ? 1u : 0u;
+  MOEV_HIP(moev::launch_unpack(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  return MOEV_OK;
+}
+
+int convert_replay(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
+                   const moev_state* state, void* stream) {
+  if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "convert_replay: null argument");
+  const auto& h = p->host;
+  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_COMPUTE] != 2)
+    return fail(MOEV_E_INVAL, "convert_replay: needs FP32 master and moments and 2-byte compute weights");
+  if (adam->step == 0) return fail(MOEV_E_INVAL, "convert_replay: step counts from 1");
+  int rc = check_state(p, state, "convert_replay");
+  if (rc != MOEV_OK) return rc;
+  void* const* table[4] = {state->master, state->m, state->v, state->compute};
+  for (uint32_t t = 0; t < h.n_tensors; ++t) {
+    if (h.tensors[t].numel == 0) continue;  // an empty tensor is never dereferenced
+    for (int k = 0; k < 4; ++k)
+      if (!table[k][t] || !aligned16(table[k][t]))
+        return fail(MOEV_E_INVAL, "convert_replay: tensor %u kind %d pointer is null or not 16-byte aligned", t, k);
+    if (!aligned16(grads[t])) return fail(MOEV_E_INVAL, "convert_replay: gradient %u is not 16-byte aligned", t);
+  }
+  std::lock_guard<std::mutex> lock(p->mu);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  std::vector<void*> g(grads, grads + h.n_tensors);
+  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s);
+  if (rc != MOEV_OK) return rc;
+
+  moev::AdamArgs a{};
+  a.tile_start = p->d_tensor_tile_start;
+  a.numel = p->d_numel;
+  a.op_of_tensor = p->d_op_of_tensor;
+  a.mask = d_active_mask;
+  a.ptrs = p->d_state_ptrs;
+  a.grads = p->d_grad_ptrs;
+  a.status = p->d_status;
+  a.n_tensors = h.n_tensors;
+  a.tile_elems = static_cast<uint32_t>(p->adam_tile_elems);
+  a.lds_entries = h.n_tensors + 1 <= moev::kMaxLdsEntries ? h.n_tensors + 1 : 0;
+  a.lr = adam->lr;
+  a.beta1 = adam->beta1;
+  a.beta2 = adam->beta2;
+  a.eps = adam->eps;
+  a.one_minus_beta1 = 1.0f - adam->beta1;
+  a.one_minus_beta2 = 1.0f - adam->beta2;
+  // bias corrections 1 - beta^step: in double, rounded to FP32 once
+  a.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta1), static_cast<double>(adam->step)));
+  a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
+  a.decay = adam->lr * adam->weight_decay;
+  a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
+  MOEV_HIP(moev::launch_adam(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
+  return MOEV_OK;
+}
+
+}  // extern "C"

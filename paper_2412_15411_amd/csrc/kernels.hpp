@@ -1,0 +1,68 @@
+// kernels.hpp -- launch interface of the gfx950 kernels (layout scan, pack gather, unpack
+// scatter, fused Adam replay).  Host code fills the argument blocks; every pointer in them
+// is a device pointer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace moev {
+
+// One segment of a packed snapshot as the kernels see it (16 bytes).
+struct SegDesc {
+  uint32_t tensor;
+  uint32_t kind;    // MOEV_KIND_*
+  uint64_t nbytes;
+};
+
+// One prefix-sum job, handled by one workgroup: over `n` items with sizes[i * stride],
+//   prefix_out[i]     = first + sum_{j<i} roundup(size_j, gran)          (optional)
+//   tile_start_out[i] = sum_{j<i} ceil(roundup(size_j, gran) / tile),  i = 0..n
+//   *total_out        = first + sum_j roundup(size_j, gran)              (optional)
+struct ScanJob {
+  const uint64_t* sizes;
+  uint64_t* prefix_out;
+  uint32_t* tile_start_out;
+  uint64_t* total_out;
+  uint64_t first, gran, tile;
+  uint32_t n, stride;
+};
+
+struct CopyArgs {
+  const SegDesc* segs;         // the slot's segments
+  const uint64_t* dst_off;     // device-computed segment offsets
+  const uint32_t* tile_start;  // [n_seg + 1] device-computed
+  void* const* ptrs;           // [4 * n_tensors]: kind-major table of dense tensor pointers
+  uint8_t* packed;
+  uint64_t header[7];          // magic, version | slot << 32, plan hash, iteration, segments, payload, align
+  uint32_t n_seg, n_tensors, tile_bytes, align;
+  uint32_t lds_entries;        // tile_start entries staged in LDS (0: search in global memory)
+  // unpack only
+  uint8_t* mask;
+  const uint32_t* slot_of_op;
+  uint32_t* status;
+  uint32_t n_ops, slot, derive_compute;
+};
+
+struct AdamArgs {
+  const uint32_t* tile_start;  // [n_tensors + 1]
+  const uint64_t* numel;
+  const uint32_t* op_of_tensor;
+  const uint8_t* mask;
+  void* const* ptrs;           // [4 * n_tensors] master, m, v, compute
+  void* const* grads;          // [n_tensors]
+  uint32_t* status;            // raised when an active operator has no gradient pointer
+  uint32_t n_tensors, tile_elems, lds_entries, has_decay;
+  float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
+};
+
+hipError_t launch_layout_scan(const ScanJob* d_jobs, uint32_t n_jobs, hipStream_t s);
+hipError_t launch_pack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
+hipError_t launch_unpack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
+hipError_t launch_adam(const AdamArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
+
+constexpr uint32_t kThreads = 256;           // 4 wavefronts of 64
+constexpr uint32_t kMaxLdsEntries = 8192;    // 32 KB of tile_start in LDS at most; larger tables are searched in global memory
+
+}  // namespace moev

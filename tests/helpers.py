@@ -35,13 +35,19 @@ def states_equal(a: "oracle.State", b: "oracle.State"):
 
 
 def max_rel_err(x: np.ndarray, ref: np.ndarray) -> float:
-    """max |x - ref| / max(|ref|, 1e-30), NaN patterns must coincide."""
+    """max |x - ref| / max(|ref|, 1e-30) over the finite reference values; NaN positions and
+    infinities must coincide exactly (otherwise the error is infinite)."""
     x = x.astype(np.float64)
     ref = ref.astype(np.float64)
     nan_x, nan_r = np.isnan(x), np.isnan(ref)
     if not np.array_equal(nan_x, nan_r):
         return float("inf")
-    ok = ~nan_r
+    inf_r = np.isinf(ref)
+    if not np.array_equal(x[inf_r], ref[inf_r]):
+        return float("inf")
+    ok = ~nan_r & ~inf_r
     if not ok.any():
         return 0.0
-    return float(np.max(np.abs(x[ok] - ref[ok]) / np.maximum(np.abs(ref[ok]), 1e-30)))
+    with np.errstate(invalid="ignore"):
+        err = np.abs(x[ok] - ref[ok]) / np.maximum(np.abs(ref[ok]), 1e-30)
+    return float(np.max(np.nan_to_num(err, nan=np.inf)))

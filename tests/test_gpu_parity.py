@@ -1,0 +1,453 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
+
+Copies (pack, drain, unpack) must agree bit for bit; replayed FP32 Adam state within a max
+relative error of 1e-6 (max |x - ref| / max(|ref|, 1e-30)); the bf16 compute weights must be
+the round-to-nearest-even cast of the GPU's own master weights and equal the oracle's wherever
+the master weights agree bitwise.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_15411_amd import binding as B
+from paper_2412_15411_amd import workloads as W
+from helpers import hp_of, model_of, np_of, state_of, states_equal, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-6
+KINDS = ("master", "m", "v", "compute")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU (no CPU fallback exists)"
+    return torch.device("cuda:0")
+
+
+# ---------------------------------------------------------------------------------------
+# helpers
+# ---------------------------------------------------------------------------------------
+GUARD = 64  # bytes of sentinel between neighbouring tensors
+
+
+class DeviceState:
+    """The workload's tensors carved out of one device arena per kind, with sentinel-filled
+    guard gaps between neighbours so that any stray write shows."""
+
+    def __init__(self, st_cpu, dev):
+        self.arena, self.views, self.spans = {}, {k: [] for k in KINDS}, {k: [] for k in KINDS}
+        for kind in KINDS:
+            offs, cursor = [], GUARD
+            for t in st_cpu[kind]:
+                cursor = (cursor + 15) // 16 * 16
+                offs.append(cursor)
+                cursor += t.numel() * t.element_size() + GUARD
+            arena = torch.full((cursor + 16,), 0x5A, dtype=torch.uint8, device=dev)
+            base = (-arena.data_ptr()) % 16  # torch allocations are far more aligned; keep it general
+            for t, o in zip(st_cpu[kind], offs):
+                nbytes = t.numel() * t.element_size()
+                view = arena[base + o: base + o + nbytes].view(t.dtype)
+                view.copy_(t)
+                self.views[kind].append(view)
+                self.spans[kind].append((base + o, nbytes))
+            self.arena[kind] = arena
+        self.state = B.State(*[self.views[k] for k in KINDS])
+
+    def guards_intact(self):
+        for kind in KINDS:
+            a = self.arena[kind].cpu().numpy()
+            keep = np.ones(a.size, dtype=bool)
+            for o, n in self.spans[kind]:
+                keep[o:o + n] = False
+            if not (a[keep] == 0x5A).all():
+                return False
+        return True
+
+    def to_oracle(self):
+        import oracle
+        return oracle.State(*[[np_of(v) for v in self.views[k]] for k in KINDS])
+
+    def poison(self):
+        for k in ("master", "m", "v"):
+            for v in self.views[k]:
+                v.view(torch.int32).fill_(0x7FC0DEAD)
+        for v in self.views["compute"]:
+            v.view(torch.int16).fill_(-1)
+
+
+def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=None, nt=None):
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
+                       align=align)
+    if tile:
+        B.moev_tune(plan, B.TUNE_COPY_TILE_BYTES, tile)
+    if blocks:
+        B.moev_tune(plan, B.TUNE_COPY_MAX_BLOCKS, blocks)
+    if adam_tile:
+        B.moev_tune(plan, B.TUNE_ADAM_TILE_ELEMS, adam_tile)
+    if adam_blocks:
+        B.moev_tune(plan, B.TUNE_ADAM_MAX_BLOCKS, adam_blocks)
+    if nt is not None:
+        B.moev_tune(plan, B.TUNE_NONTEMPORAL, nt)
+    return plan
+
+
+def packed_buffer(plan, dev, slot=None):
+    n = B.ckpt_plan_max_packed_bytes(plan) if slot is None else B.ckpt_plan_packed_bytes(plan, slot)
+    buf = torch.full((n + 256,), 0xA5, dtype=torch.uint8, device=dev)
+    assert buf.data_ptr() % 256 == 0
+    return buf
+
+
+def ragged_workload(seed, n_ops=11, window=4, max_numel=70000, with_empty=True):
+    rng = np.random.default_rng(seed)
+    tensors = []
+    for e in range(n_ops):
+        for _ in range(int(rng.integers(1, 4))):
+            n = int(rng.integers(1, max_numel))
+            if rng.random() < 0.3:
+                n = int(rng.integers(1, 40))          # tiny tensors: many sub-vector tails
+            tensors.append((e, n))
+    if with_empty:
+        tensors[3] = (tensors[3][0], 0)
+    slots = [int(x) for x in rng.integers(0, window, size=n_ops)]
+    slots[0], slots[1] = 0, window - 1
+    return W.Workload(f"ragged{seed}", tensors, slots, window)
+
+
+# ---------------------------------------------------------------------------------------
+# layout scan
+# ---------------------------------------------------------------------------------------
+def _many_segments():
+    n_ops = 9000
+    rng = np.random.default_rng(0)
+    return W.Workload("many", [(e, int(rng.integers(1, 40))) for e in range(n_ops)], [e % 2 for e in range(n_ops)], 2)
+
+
+@pytest.mark.parametrize("wl,align,tile", [
+    (ragged_workload(1), 16, 4096), (ragged_workload(2), 256, 32768), (ragged_workload(3), 4096, 8192),
+    (W.fine_grained_stack(n_layers=2, n_routed=64, n_shared=2, d_model=16, d_ff=11), 256, 4096),
+    (_many_segments(), 64, 4096),
+], ids=["ragged16", "ragged256", "ragged4096", "c2_small_888seg", "18000seg"])
+def test_device_layout_scan_matches_oracle(orc, dev, wl, align, tile):
+    """The wavefront prefix sums on the device reproduce the oracle's serial layout exactly."""
+    plan = make_plan(wl, align=align, tile=tile)
+    model = model_of(wl, align=align)
+    for k in range(wl.window):
+        segs, total = orc.layout(model, k)
+        off, tiles, dev_total = B.ckpt_plan_device_layout(plan, k)
+        assert off == [s[3] for s in segs]
+        assert dev_total == total == B.ckpt_plan_packed_bytes(plan, k)
+        exp_tiles = [0]
+        for s in segs:
+            padded = -(-s[2] // align) * align
+            exp_tiles.append(exp_tiles[-1] + -(-padded // tile))
+        assert tiles == exp_tiles
+
+
+# ---------------------------------------------------------------------------------------
+# pack / drain / unpack
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,align,tile,blocks,nt", [
+    (1, 256, 32768, None, 1), (2, 16, 4096, 3, 1), (3, 4096, 8192, 7, 0), (4, 64, 65536, 1, 1), (5, 256, 32768, None, 0),
+])
+def test_pack_bit_exact(orc, dev, seed, align, tile, blocks, nt):
+    """Ragged tensors with arbitrary bit patterns: GPU packed buffer == oracle packed buffer, byte
+    for byte (header, segments, zero padding), for every slot; the source state is not modified."""
+    wl = ragged_workload(seed)
+    st_cpu = W.random_bits_state(wl, seed=seed)
+    ds = DeviceState(st_cpu, dev)
+    ref_state = state_of(st_cpu)
+    plan, model = make_plan(wl, align=align, tile=tile, blocks=blocks, nt=nt), model_of(wl, align=align)
+    buf = packed_buffer(plan, dev)
+    for k in range(wl.window):
+        buf.fill_(0xA5)
+        B.snapshot_pack(plan, k, 100 + k, ds.state, buf, cap=B.ckpt_plan_packed_bytes(plan, k))
+        torch.cuda.synchronize()
+        exp = orc.pack(model, k, 100 + k, ref_state)
+        got = buf.cpu().numpy()
+        assert got[:exp.size].tobytes() == exp.tobytes(), f"slot {k}"
+        assert (got[exp.size:] == 0xA5).all()           # nothing written past the snapshot
+    assert states_equal(ds.to_oracle(), ref_state) == [] and ds.guards_intact()
+
+
+@pytest.mark.parametrize("seed,align,tile,blocks", [(11, 256, 32768, None), (12, 16, 4096, 5), (13, 4096, 16384, 2)])
+def test_unpack_bit_exact_with_sentinels(orc, dev, seed, align, tile, blocks):
+    """restore_unpack of an ORACLE-made snapshot into a poisoned device state equals the oracle's
+    unpack: restored tensors, derived bf16 weights of the newly active operators, untouched
+    tensors, guard gaps and the active mask."""
+    wl = ragged_workload(seed)
+    model = model_of(wl, align=align)
+    truth = state_of(W.random_bits_state(wl, seed=seed))
+    plan = make_plan(wl, align=align, tile=tile, blocks=blocks)
+    st_cpu = W.random_bits_state(wl, seed=seed + 100)
+    for k in range(wl.window):
+        ds = DeviceState(st_cpu, dev)
+        ds.poison()
+        ref = ds.to_oracle()
+        snap = orc.pack(model, k, 50 + k, truth)
+        ref_mask = np.full(wl.n_ops, 9, dtype=np.uint8)
+        orc.unpack(model, k, snap, ref, ref_mask)
+        buf = packed_buffer(plan, dev, k)
+        buf[:snap.size].copy_(torch.from_numpy(snap))
+        mask = torch.full((wl.n_ops,), 9, dtype=torch.uint8, device=dev)
+        B.restore_unpack(plan, k, None, buf, ds.state, mask)
+        torch.cuda.synchronize()
+        B.ckpt_plan_device_status(plan)
+        assert states_equal(ds.to_oracle(), ref) == [], f"slot {k}"
+        assert ds.guards_intact()
+        assert np.array_equal(mask.cpu().numpy(), ref_mask)
+
+
+def test_pack_drain_restore_roundtrip_through_pinned_host(orc, dev):
+    """pack -> drain (side stream, event-ordered) -> host bytes equal the oracle's snapshot;
+    restore from the pinned copy (H2D + scatter) brings a poisoned state back: identity."""
+    wl = ragged_workload(21, max_numel=200000)
+    model = model_of(wl)
+    st_cpu = W.make_state(wl, seed=3)
+    ds = DeviceState(st_cpu, dev)
+    ref_state = state_of(st_cpu)
+    plan = make_plan(wl)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    buf = packed_buffer(plan, dev)
+    host = torch.empty(B.ckpt_plan_max_packed_bytes(plan), dtype=torch.uint8).pin_memory()
+    for k in range(wl.window):
+        packed_done, drained = torch.cuda.Event(), torch.cuda.Event()
+        with torch.cuda.stream(main):
+            B.snapshot_pack(plan, k, 7 + k, ds.state, buf, stream=main)
+            packed_done.record(main)
+        drained.record(side)  # create the event handle before handing it to the library
+        B.snapshot_drain(plan, k, buf, host, side_stream=side, pack_done=packed_done, drained=drained)
+        drained.synchronize()
+        n = B.ckpt_plan_packed_bytes(plan, k)
+        exp = orc.pack(model, k, 7 + k, ref_state)
+        assert host.numpy()[:n].tobytes() == exp.tobytes()
+        assert B.snapshot_peek(plan, k, host)["iter"] == 7 + k
+        # restore into a poisoned copy through the host path
+        target = DeviceState(st_cpu, dev)
+        target.poison()
+        ref = target.to_oracle()
+        ref_mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        orc.unpack(model, k, exp, ref, ref_mask)
+        mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+        buf2 = packed_buffer(plan, dev, k)
+        B.restore_unpack(plan, k, host, buf2, target.state, mask, stream=main)
+        main.synchronize()
+        assert states_equal(target.to_oracle(), ref) == [] and target.guards_intact()
+        assert np.array_equal(mask.cpu().numpy(), ref_mask)
+        main.synchronize()
+        side.synchronize()
+
+
+def test_foreign_snapshots_are_refused(orc, dev):
+    """Host path: MISMATCH before anything is enqueued.  Device path: the kernel skips the scatter
+    and raises the status word; the state stays as it was."""
+    wl = ragged_workload(31)
+    model, plan = model_of(wl), make_plan(wl)
+    st_cpu = W.random_bits_state(wl, seed=1)
+    ds = DeviceState(st_cpu, dev)
+    before = ds.to_oracle()
+    snap1 = orc.pack(model, 1, 5, state_of(st_cpu))
+    host = torch.from_numpy(snap1.copy()).pin_memory()
+    buf = packed_buffer(plan, dev)
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    with pytest.raises(B.MoevError) as e:
+        B.restore_unpack(plan, 0, host, buf, ds.state, mask)      # slot-1 snapshot offered as slot 0
+    assert e.value.code == B.E_MISMATCH
+    buf.zero_()
+    buf[:snap1.size].copy_(torch.from_numpy(snap1))
+    B.restore_unpack(plan, 2, None, buf, ds.state, mask)          # device-resident, wrong slot
+    torch.cuda.synchronize()
+    with pytest.raises(B.MoevError) as e:
+        B.ckpt_plan_device_status(plan)
+    assert e.value.code == B.E_MISMATCH
+    B.ckpt_plan_device_status(plan)                               # reading cleared it
+    assert states_equal(ds.to_oracle(), before) == [] and not mask.any().item()
+
+
+def test_host_side_argument_checks(dev):
+    wl = W.tiny_moe(d_in=8, d_hidden=16)
+    plan = make_plan(wl)
+    st = W.make_state(wl, seed=0, device=dev)
+    state = B.State(st["master"], st["m"], st["v"], st["compute"])
+    buf = packed_buffer(plan, dev)
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_pack(plan, wl.window, 0, state, buf)
+    assert e.value.code == B.E_RANGE
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_pack(plan, 0, 0, state, buf, cap=B.ckpt_plan_packed_bytes(plan, 0) - 1)
+    assert e.value.code == B.E_RANGE
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_pack(plan, 0, 0, state, buf.data_ptr() + 16, cap=buf.numel() - 16)
+    assert e.value.code == B.E_INVAL
+    skew = [t for t in st["master"]]
+    skew[0] = torch.empty(skew[0].numel() + 4, dtype=torch.float32, device=dev)[1:1 + skew[0].numel()]
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_pack(plan, 0, 0, B.State(skew, st["m"], st["v"], st["compute"]), buf)
+    assert e.value.code == B.E_INVAL
+    mask = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    grads = W.make_grads(wl, 11, device=dev)
+    with pytest.raises(B.MoevError) as e:
+        B.convert_replay(plan, 1e-4, 0.9, 0.95, 1e-8, 0.0, 0, mask, grads, state)   # step counts from 1
+    assert e.value.code == B.E_INVAL
+    # an active operator without gradients is skipped and reported, never dereferenced
+    grads[0] = None
+    before = st["master"][0].clone()
+    B.convert_replay(plan, 1e-4, 0.9, 0.95, 1e-8, 0.0, 11, mask, grads, state)
+    torch.cuda.synchronize()
+    with pytest.raises(B.MoevError) as e:
+        B.ckpt_plan_device_status(plan)
+    assert e.value.code == B.E_INVAL and torch.equal(before, st["master"][0])
+
+
+# ---------------------------------------------------------------------------------------
+# Adam replay
+# ---------------------------------------------------------------------------------------
+def _compare_adam(ds, ref, label=""):
+    got = ds.to_oracle()
+    worst = 0.0
+    for kind in ("master", "m", "v"):
+        for t, (x, y) in enumerate(zip(got.kinds()[kind], ref.kinds()[kind])):
+            err = max_rel_err(x, y)
+            assert err <= REL_TOL, f"{label} {kind}[{t}] max rel err {err}"
+            worst = max(worst, err)
+    import oracle
+    for t, (c, p, cr, pr) in enumerate(zip(got.compute, got.master, ref.compute, ref.master)):
+        same = p.view(np.uint32) == pr.view(np.uint32)
+        assert np.array_equal(c[same], cr[same]), f"{label} compute[{t}]"
+        if not same.all():  # where the master differs in the last bits, compute must be the cast of the GPU's own master
+            idx = np.nonzero(~same)[0][:64]
+            assert np.array_equal(c[idx], oracle.bf16_rne_array(p[idx]))
+    return worst
+
+
+@pytest.mark.parametrize("seed,wd,heavy,adam_tile,blocks,nt", [
+    (1, 0.0, False, 8192, None, 1), (2, 0.1, True, 1024, 3, 1), (3, 0.0, True, 4096, 1, 0), (4, 0.01, False, 16384, 9, 0),
+])
+def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt):
+    """One replayed iteration on ragged tensors with a mixed active/frozen mask: FP32 state within
+    1e-6 relative of the oracle (expected bit-identical), frozen tensors and guards untouched."""
+    wl = ragged_workload(40 + seed)
+    wl.weight_decay, wl.heavy_tail = wd, heavy
+    model, hp = model_of(wl), hp_of(wl)
+    st_cpu = W.make_state(wl, seed=seed)
+    ds = DeviceState(st_cpu, dev)
+    ref = state_of(st_cpu)
+    plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt)
+    rng = np.random.default_rng(seed)
+    mask_np = (rng.random(wl.n_ops) < 0.6).astype(np.uint8)
+    mask_np[0] = 1
+    mask = torch.from_numpy(mask_np).to(dev)
+    for step in (11, 12, 13):
+        grads_cpu = W.make_grads(wl, step, seed=seed)
+        grads_dev = [g.to(dev) for g in grads_cpu]
+        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, step, mask, grads_dev, ds.state)
+        torch.cuda.synchronize()
+        orc.replay_step(model, hp, step, mask_np, [np_of(g) for g in grads_cpu], ref)
+    B.ckpt_plan_device_status(plan)
+    worst = _compare_adam(ds, ref, "ragged")
+    assert ds.guards_intact()
+    exact = states_equal(ds.to_oracle(), ref) == []
+    print(f"adam seed {seed}: worst rel err {worst:.3g}, bit-identical={exact}")
+
+
+def test_adam_special_values(orc, dev):
+    """NaN / Inf / denormal / zero inputs propagate exactly as in the oracle (no flushing)."""
+    n = 4096 + 3
+    wl = W.Workload("special", [(0, n)], [0], 1)
+    model, hp = model_of(wl), hp_of(wl)
+    st_cpu = W.make_state(wl, seed=9)
+    specials = torch.tensor([0.0, -0.0, float("inf"), -float("inf"), float("nan"), 1e-45, -1e-45, 1e-39, 3e38, -3e38,
+                             1.17549435e-38, 1e-20], dtype=torch.float32)
+    g = W.make_grads(wl, 11, seed=9)[0]
+    k = specials.numel()
+    st_cpu["master"][0][:k] = specials
+    st_cpu["m"][0][k:2 * k] = specials
+    st_cpu["v"][0][2 * k:3 * k] = specials.abs()
+    g[3 * k:4 * k] = specials
+    g[4 * k:5 * k] = 0.0
+    st_cpu["v"][0][4 * k:5 * k] = 0.0
+    st_cpu["m"][0][4 * k:5 * k] = 0.0        # 0/(0+eps) = 0
+    ds = DeviceState(st_cpu, dev)
+    ref = state_of(st_cpu)
+    plan = make_plan(wl)
+    mask = torch.ones(1, dtype=torch.uint8, device=dev)
+    B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, 11, mask, [g.to(dev)], ds.state)
+    torch.cuda.synchronize()
+    orc.replay_step(model, hp, 11, np.ones(1, dtype=np.uint8), [np_of(g)], ref)
+    _compare_adam(ds, ref, "special")
+    got = ds.to_oracle()
+    for kind in ("master", "m", "v"):
+        assert np.array_equal(np.isnan(got.kinds()[kind][0]), np.isnan(ref.kinds()[kind][0]))
+
+
+# ---------------------------------------------------------------------------------------
+# whole window: snapshots during a dense run, then sparse-to-dense conversion
+# ---------------------------------------------------------------------------------------
+def _gpu_window(orc, dev, wl, seed, align=256, via_host=False, **tune):
+    """Dense GPU run with per-iteration snapshots, then GPU conversion from them; returns the GPU's
+    converted state, the oracle's dense-run state and the oracle's snapshots."""
+    model, hp = model_of(wl, align=align), hp_of(wl)
+    st_cpu = W.make_state(wl, seed=seed)
+    grads_cpu = {t: W.make_grads(wl, t, seed=seed) for t in range(wl.t0 + 1, wl.t0 + wl.window + 1)}
+    grads_dev = {t: [g.to(dev) for g in gs] for t, gs in grads_cpu.items()}
+    # oracle: dense truth + snapshots
+    dense = state_of(st_cpu)
+    snaps = orc.dense_run(model, dense, hp, lambda t: [np_of(g) for g in grads_cpu[t]], wl.t0, wl.window, snapshots=True)
+    # GPU: same dense run, snapshot SS_{t0+k} packed from the state after step t0+k
+    plan = make_plan(wl, align=align, **tune)
+    live = DeviceState(st_cpu, dev)
+    everyone = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    bufs = []
+    for k in range(wl.window):
+        buf = packed_buffer(plan, dev, k)
+        B.snapshot_pack(plan, k, wl.t0 + k, live.state, buf)
+        bufs.append(buf)
+        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + k + 1, everyone,
+                         grads_dev[wl.t0 + k + 1], live.state)
+    torch.cuda.synchronize()
+    for k in range(wl.window):
+        assert bufs[k].cpu().numpy()[:snaps[k].size].tobytes() == snaps[k].tobytes(), f"snapshot {k}"
+    # GPU: conversion into a poisoned state
+    rebuilt = DeviceState(st_cpu, dev)
+    rebuilt.poison()
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    for i in range(wl.window):
+        host = None
+        if via_host:
+            host = bufs[i].cpu().pin_memory()
+            bufs[i].fill_(0)
+        B.restore_unpack(plan, i, host, bufs[i], rebuilt.state, mask)
+        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + i + 1, mask,
+                         grads_dev[wl.t0 + i + 1], rebuilt.state)
+        torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan)
+    assert mask.all().item()
+    return rebuilt, live, dense
+
+
+def test_window_tiny_config(orc, dev):
+    """configs[0]: snapshots bit-exact, converted state == the GPU's own dense run bitwise and
+    within 1e-6 relative of the oracle's brute-force dense Adam run."""
+    wl = W.tiny_moe()
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=0)
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "c0")
+    assert rebuilt.guards_intact() and live.guards_intact()
+
+
+def test_window_conversion_stress_small(orc, dev):
+    """A shrunken configs[4]: 2 layers x (16 routed + 2 shared), W = 8, permuted schedule, heavy-tailed
+    gradients, restore through pinned host memory."""
+    wl = W.conversion_stress(n_layers=2, n_routed=16, n_shared=2, d_model=64, d_ff=44, per_slot=2)
+    assert wl.window == 8
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=4, via_host=True, tile=4096, adam_tile=1024)
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "c4-small")
+
+
+def test_window_ragged_small_grid(orc, dev):
+    wl = ragged_workload(77, n_ops=9, window=3, with_empty=True)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=5, align=16, tile=4096, blocks=2, adam_tile=1024, adam_blocks=2)
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "ragged-window")

@@ -1,0 +1,182 @@
+"""CPU tests of the HIP library's host side: it loads, exports every declared symbol, and its
+plan (schedule, segment tables, sizes, hash) agrees with the oracle.  No GPU compute calls."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2412_15411_amd import binding as B
+from paper_2412_15411_amd import workloads as W
+from helpers import model_of
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "moev.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text))
+    declared -= {"defined"}
+    assert {"ckpt_plan", "snapshot_pack", "snapshot_drain", "restore_unpack", "convert_replay"} <= declared
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in moev.h but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+def _plan_of(wl, mode="explicit", align=0, widths=(0, 0, 0), n_active=0):
+    if mode == "explicit":
+        return B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, align=align,
+                           widths=widths)
+    return B.ckpt_plan(wl.tensors, B.FIXED, n_active=n_active, order=wl.order, align=align, widths=widths)
+
+
+def _cases():
+    rng = np.random.default_rng(12)
+    ragged_tensors = []
+    for e in range(9):
+        for _ in range(int(rng.integers(1, 4))):
+            ragged_tensors.append((e, int(rng.integers(0, 5000))))
+    ragged = W.Workload("ragged", ragged_tensors, [int(x) for x in rng.integers(0, 4, size=9)], 4)
+    return [
+        W.tiny_moe(),
+        W.mixtral_layer(d_model=64, d_ff=224),
+        W.fine_grained_stack(n_layers=2, n_routed=16, n_shared=2, d_model=32, d_ff=22, per_slot=4),
+        W.ep_rank_share(n_layers=3, n_experts=8, d_model=16, d_ff=8, per_slot=2),
+        ragged,
+        W.fine_grained_stack(),   # full-size configs: table sizes only, nothing is allocated
+        W.ep_rank_share(),
+    ]
+
+
+@pytest.mark.parametrize("wl", _cases(), ids=lambda w: w.name)
+@pytest.mark.parametrize("align", [16, 256, 4096])
+def test_plan_matches_oracle(orc, wl, align):
+    plan = _plan_of(wl, align=align)
+    model = model_of(wl, align=align)
+    assert B.ckpt_plan_window(plan) == wl.window
+    assert B.ckpt_plan_n_ops(plan) == wl.n_ops and B.ckpt_plan_n_tensors(plan) == wl.n_tensors
+    assert B.ckpt_plan_slot_of_op(plan) == list(wl.slot_of_op)
+    assert B.ckpt_plan_order(plan) == list(wl.order)
+    assert orc.check_schedule(B.ckpt_plan_order(plan), B.ckpt_plan_slot_of_op(plan), wl.window) == orc.OK
+    assert B.ckpt_plan_hash(plan) == orc.plan_hash(model)
+    biggest = 0
+    for k in range(wl.window):
+        segs, total = orc.layout(model, k)
+        assert B.ckpt_plan_segments(plan, k) == segs
+        assert B.ckpt_plan_n_segments(plan, k) == len(segs)
+        assert B.ckpt_plan_packed_bytes(plan, k) == total
+        biggest = max(biggest, total)
+        assert B.ckpt_plan_active_params(plan, k) == wl.active_params_at(k)
+    assert B.ckpt_plan_max_packed_bytes(plan) == biggest
+    assert B.ckpt_plan_packed_bytes(plan, wl.window) == 0
+
+
+def test_fixed_mode_matches_generate_schedule(orc):
+    for n, a, seed in [(6, 2, 0), (13, 4, 1), (8, 1, 2), (66, 66, 3), (7, 3, 4)]:
+        order = W.seeded_permutation(n, seed)
+        tensors = [(e, 10 + e) for e in range(n)]
+        plan = B.ckpt_plan(tensors, B.FIXED, n_active=a, order=order)
+        slots, window = orc.generate_schedule(order, a)
+        assert B.ckpt_plan_window(plan) == window and B.ckpt_plan_slot_of_op(plan) == slots
+        assert B.ckpt_plan_order(plan) == order and B.ckpt_plan_n_active(plan) == a
+        model = orc.Model(tensors, order, slots, window)
+        assert B.ckpt_plan_hash(plan) == orc.plan_hash(model)
+        for k in range(window):
+            assert B.ckpt_plan_segments(plan, k) == orc.layout(model, k)[0]
+
+
+def test_auto_mode_follows_algorithm_1(orc):
+    rng = np.random.default_rng(8)
+    for _ in range(100):
+        n = int(rng.integers(1, 70))
+        bw = float(rng.uniform(1e9, 6e10))
+        t_iter = float(rng.uniform(1e-3, 3.0))
+        per_op = int(rng.integers(1000, 5_000_000))
+        w, a = B.moev_find_window_size(n, t_iter, 2.0 * per_op, 4.0 * per_op, 8.0 * per_op, bw)
+        assert (w, a) == orc.find_window_size(n, t_iter, 2.0 * per_op, 4.0 * per_op, 8.0 * per_op, bw)
+        plan = B.ckpt_plan([(e, per_op) for e in range(n)], B.AUTO, t_iter_s=t_iter, host_link_Bps=bw)
+        assert B.ckpt_plan_window(plan) == w and B.ckpt_plan_n_active(plan) == a
+        assert B.ckpt_plan_slot_of_op(plan) == orc.generate_schedule(list(range(n)), a)[0]
+
+
+def test_order_operators_and_reorder_trigger(orc):
+    rng = np.random.default_rng(2)
+    for _ in range(30):
+        pop = [float(x) for x in rng.integers(0, 7, size=int(rng.integers(1, 50)))]
+        assert B.moev_order_operators(pop) == orc.order_by_popularity(pop)
+    # Sec. 3.5: re-order when the frequency moved by more than 10% for at least 25% of the experts
+    old = [100.0] * 8
+    assert not B.moev_reorder_needed(old, [100.0] * 6 + [120.0, 80.0][:1] + [100.0])   # 1 of 8 moved
+    assert B.moev_reorder_needed(old, [100.0] * 6 + [120.0, 80.0])                      # 2 of 8 = 25%
+    assert not B.moev_reorder_needed(old, [109.0] * 8)                                   # all within 10%
+    assert B.moev_reorder_needed(old, [111.0] * 8)
+
+
+def test_plan_rejects_bad_configurations():
+    t = [(0, 10), (1, 10), (2, 10)]
+    bad = [
+        dict(tensors=[(0, 10), (2, 10)], mode=B.EXPLICIT, window=2, slot_of_op=[0, 1, 1]),   # operator 1 has no tensor
+        dict(tensors=[(1, 10), (0, 10)], mode=B.EXPLICIT, window=2, slot_of_op=[0, 1]),      # not grouped ascending
+        dict(tensors=t, mode=B.EXPLICIT, window=2, slot_of_op=[0, 1, 2]),                    # slot outside the window
+        dict(tensors=t, mode=B.EXPLICIT, window=0, slot_of_op=[0, 0, 0]),
+        dict(tensors=t, mode=B.EXPLICIT, window=3, slot_of_op=[0, 1, 2], order=[2, 1, 0]),   # order walks back
+        dict(tensors=t, mode=B.FIXED, n_active=0),
+        dict(tensors=t, mode=B.FIXED, n_active=2, order=[0, 1, 1]),                          # not a permutation
+        dict(tensors=t, mode=B.AUTO, t_iter_s=1.0, host_link_Bps=0.0),
+        dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], align=48),          # not a power of two
+        dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], align=8),
+        dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], widths=(3, 4, 2)),
+        dict(tensors=t, mode=7),
+    ]
+    for kw in bad:
+        with pytest.raises(B.MoevError) as e:
+            B.ckpt_plan(**kw)
+        assert e.value.code == B.E_INVAL, kw
+
+
+def test_tune_knobs_validate():
+    plan = _plan_of(W.tiny_moe())
+    assert B.moev_tune_get(plan, B.TUNE_COPY_TILE_BYTES) % 4096 == 0
+    B.moev_tune(plan, B.TUNE_COPY_TILE_BYTES, 65536)
+    assert B.moev_tune_get(plan, B.TUNE_COPY_TILE_BYTES) == 65536
+    for knob, value in [(B.TUNE_COPY_TILE_BYTES, 1000), (B.TUNE_ADAM_TILE_ELEMS, 100), (B.TUNE_COPY_MAX_BLOCKS, -1), (99, 1)]:
+        with pytest.raises(B.MoevError):
+            B.moev_tune(plan, knob, value)
+
+
+def test_snapshot_peek_accepts_oracle_snapshot_and_rejects_others(orc):
+    """The header the oracle writes is the header the library expects (format is shared by definition)."""
+    import torch
+    from helpers import state_of
+    wl = W.tiny_moe(d_in=8, d_hidden=16)
+    plan, model = _plan_of(wl), model_of(wl)
+    st = state_of(W.make_state(wl, seed=1))
+    snap = orc.pack(model, 1, 77, st)
+    buf = torch.from_numpy(snap)
+    hd = B.snapshot_peek(plan, 1, buf)
+    assert hd["iter"] == 77 and hd["slot"] == 1 and hd["n_segments"] == len(orc.layout(model, 1)[0])
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_peek(plan, 0, buf)
+    assert e.value.code == B.E_MISMATCH
+    other = _plan_of(wl, align=512)
+    with pytest.raises(B.MoevError):
+        B.snapshot_peek(other, 1, buf)
+
+
+def test_gpu_calls_fail_loudly_without_a_gpu():
+    """No silent fallback: on a machine without a usable GPU the hot-path calls raise."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    wl = W.tiny_moe(d_in=8, d_hidden=16)
+    plan = _plan_of(wl)
+    st = W.make_state(wl, seed=0)
+    state = B.State(st["master"], st["m"], st["v"], st["compute"])
+    packed = torch.zeros(B.ckpt_plan_max_packed_bytes(plan) + 512, dtype=torch.uint8)
+    addr = (packed.data_ptr() + 255) // 256 * 256
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_pack(plan, 0, 10, state, addr, cap=B.ckpt_plan_max_packed_bytes(plan))
+    assert e.value.code == B.E_HIP
