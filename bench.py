@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--no-drain", action="store_true", help="skip the host-link drain measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--overlap", action="store_true", help="also time the drain under a concurrent bf16 GEMM loop")
+    ap.add_argument("--persistent", action="store_true", help="fixed-grid launch shape (LDS-staged tile table)")
     ap.add_argument("--copy-tile", type=int, default=0)
     ap.add_argument("--adam-tile", type=int, default=0)
     ap.add_argument("--copy-blocks", type=int, default=0)
@@ -159,10 +160,16 @@ def main():
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
     st = W.make_state(wl, seed=args.seed, device=dev)
     state = B.State(st["master"], st["m"], st["v"], st["compute"])
+    # Gradients of replay iteration i exist only for the operators that are active in it: frozen
+    # operators skip their weight-gradient computation (Sec. 3.3), so their entries are None.
     grads = {}
     for i in range(wl.window):
-        grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev)
+        full = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev)
+        grads[wl.t0 + i + 1] = [g if wl.slot_of_op[wl.tensors[t][0]] <= i else None for t, g in enumerate(full)]
+        del full
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+    if args.persistent:
+        B.moev_tune(plan, B.TUNE_PERSISTENT, 1)
     for knob, val in ((B.TUNE_COPY_TILE_BYTES, args.copy_tile), (B.TUNE_ADAM_TILE_ELEMS, args.adam_tile),
                       (B.TUNE_COPY_MAX_BLOCKS, args.copy_blocks), (B.TUNE_ADAM_MAX_BLOCKS, args.adam_blocks)):
         if val:
@@ -228,7 +235,8 @@ def main():
                          "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
                          "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
     dominant = max(per_kind, key=lambda k: per_kind[k]["ms"])
-    kname = {"pack": "k_pack", "unpack": "k_unpack", "replay": "k_adam"}[dominant]
+    suffix = "_persistent" if args.persistent else "_direct"
+    kname = {"pack": "k_pack", "unpack": "k_unpack", "replay": "k_adam"}[dominant] + suffix
     roofline = {"bound": "hbm", "kernel": kname, "achieved": kernels[dominant]["GBs"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": kernels[dominant]["frac_hbm_peak"],
                 "traffic": read_traffic(kname, args.config)}

@@ -128,14 +128,25 @@ typedef struct {
   uint32_t align;
 } moev_header;
 
-/* launch knobs for moev_tune() */
+/* launch knobs for moev_tune().  Two launch shapes exist for pack, unpack and replay:
+ *   one tile per workgroup (default): grid = number of tiles, tile = threads x 16 bytes (4 elements
+ *     for the replay) x unroll; fastest when the kernel has the GPU to itself;
+ *   fixed grid (MOEV_TUNE_PERSISTENT = 1): at most *_MAX_BLOCKS workgroups of 256 threads walk the
+ *     tile list, tile table staged in LDS; lower the cap to leave compute units to a concurrent kernel.
+ * Changing a knob while GPU work of the plan is in flight is not allowed. */
 enum {
-  MOEV_TUNE_COPY_TILE_BYTES = 0, /* bytes of packed buffer one workgroup handles per step (multiple of 4096) */
-  MOEV_TUNE_COPY_MAX_BLOCKS = 1, /* cap on the pack/unpack grid (0 = 8 per compute unit); lower it to leave
-                                    compute units to concurrent kernels */
-  MOEV_TUNE_ADAM_TILE_ELEMS = 2, /* elements one workgroup handles per step (multiple of 1024) */
+  MOEV_TUNE_COPY_TILE_BYTES = 0, /* fixed grid: bytes of packed buffer per tile (multiple of 4096) */
+  MOEV_TUNE_COPY_MAX_BLOCKS = 1, /* fixed grid: cap on the pack/unpack grid (0 = 8 per compute unit) */
+  MOEV_TUNE_ADAM_TILE_ELEMS = 2, /* fixed grid: elements per tile (multiple of 1024) */
   MOEV_TUNE_ADAM_MAX_BLOCKS = 3,
-  MOEV_TUNE_NONTEMPORAL = 4      /* 1 = streaming (nontemporal) loads and stores, 0 = default caching */
+  MOEV_TUNE_NONTEMPORAL = 4,     /* 1 = streaming (nontemporal) loads and stores, 0 = default caching */
+  MOEV_TUNE_PERSISTENT = 5,      /* 0 = one tile per workgroup, 1 = fixed grid */
+  MOEV_TUNE_COPY_THREADS = 6,    /* one tile per workgroup: threads (64..1024) and accesses per lane (1, 2, 4); */
+  MOEV_TUNE_COPY_UNROLL = 7,     /*   supported pairs: (64|128|256|512|1024, 1), (256|512, 2), (256, 4) */
+  MOEV_TUNE_ADAM_THREADS = 8,
+  MOEV_TUNE_ADAM_UNROLL = 9,
+  MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */
+  MOEV_TUNE_UNPACK_UNROLL = 11
 };
 
 const char *moev_last_error(void);
@@ -240,6 +251,15 @@ int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d
  * Requires element widths 4, 4, 2.  Errors: MOEV_E_INVAL, MOEV_E_HIP. */
 int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
                    void *const *grads, const moev_state *state, void *stream);
+
+/* ---- measurement hook --------------------------------------------------------------------
+ * moev_copy_probe: plain contiguous device-to-device copy of nbytes (multiple of 16, both
+ * pointers 16-byte aligned) with the same access shape as the gather kernel.  It is the
+ * yardstick the pack/unpack throughput is compared with and the known-size kernel against
+ * which HBM traffic counters are calibrated.  blocks = 0: one 4 KB tile per workgroup (the default
+ * gather shape); blocks > 0: a fixed grid of that many workgroups, 32 KB per step. */
+int moev_copy_probe(void *d_dst, const void *d_src, size_t nbytes, uint32_t blocks, int nontemporal,
+                    void *stream);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,9 @@ OK, E_INVAL, E_NOMEM, E_RANGE, E_MISMATCH, E_HIP = 0, -1, -2, -3, -4, -5
 KIND_MASTER, KIND_ADAM_M, KIND_ADAM_V, KIND_COMPUTE = 0, 1, 2, 3
 EXPLICIT, FIXED, AUTO = 0, 1, 2
 HEADER_BYTES = 256
-TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL = range(5)
+(TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL,
+ TUNE_PERSISTENT, TUNE_COPY_THREADS, TUNE_COPY_UNROLL, TUNE_ADAM_THREADS, TUNE_ADAM_UNROLL,
+ TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL) = range(12)
 
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",
@@ -26,7 +28,7 @@ EXPORTS = [
     "ckpt_plan_hash", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
-    "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay",
+    "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "moev_copy_probe",
 ]
 
 
@@ -110,6 +112,7 @@ def _load():
     lib.snapshot_peek.argtypes = [vp, u32, vp, C.POINTER(_Header)]
     lib.restore_unpack.argtypes = [vp, u32, vp, vp, C.POINTER(_State), vp, vp]
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
+    lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
     return lib
 
 
@@ -308,3 +311,7 @@ def convert_replay(plan, lr, beta1, beta2, eps, weight_decay, step: int, d_activ
     g = _ptr_array(grads)
     _check(_lib.convert_replay(plan.handle, C.byref(adam), _addr(d_active_mask), g, C.byref(state.c),
                                _stream(stream)))
+
+
+def moev_copy_probe(d_dst, d_src, nbytes: int, blocks: int = 0, nontemporal: int = 1, stream=None):
+    _check(_lib.moev_copy_probe(_addr(d_dst), _addr(d_src), nbytes, blocks, nontemporal, _stream(stream)))

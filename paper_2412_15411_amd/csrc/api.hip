@@ -53,11 +53,19 @@ struct moev_plan {
   std::mutex mu;
 
   // launch knobs
-  int64_t copy_tile_bytes = 32768;
+  int64_t persistent = 0;            // 0: one tile per workgroup, 1: fixed grid walking the tile list
+  int64_t copy_threads = 256, copy_unroll = 1;   // one-tile-per-workgroup shape of the pack
+  int64_t unpack_threads = 256, unpack_unroll = 2;  // ... of the unpack
+  int64_t adam_threads = 64, adam_unroll = 1;
+  int64_t copy_tile_bytes = 32768;   // fixed-grid shape
   int64_t copy_max_blocks = 0;
   int64_t adam_tile_elems = 8192;
   int64_t adam_max_blocks = 0;
   int64_t nontemporal = 1;
+
+  uint64_t eff_copy_tile() const { return persistent ? copy_tile_bytes : copy_threads * 16 * copy_unroll; }
+  uint64_t eff_unpack_tile() const { return persistent ? copy_tile_bytes : unpack_threads * 16 * unpack_unroll; }
+  uint64_t eff_adam_tile() const { return persistent ? adam_tile_elems : adam_threads * 4 * adam_unroll; }
 
   // device side
   int device = -1;
@@ -68,12 +76,14 @@ struct moev_plan {
   char* d_tables = nullptr;       // one allocation holding every static table
   moev::SegDesc* d_segs = nullptr;
   uint64_t* d_dst_off = nullptr;
-  uint32_t* d_seg_tile_start = nullptr;     // per slot: n_segments + 1 entries
+  uint32_t* d_seg_tile_start = nullptr;     // per slot: n_segments + 1 entries (pack tiles)
+  uint32_t* d_seg_tile_start_unpack = nullptr;  // same for the unpack's tile size
   uint64_t* d_slot_total = nullptr;
   uint64_t* d_numel = nullptr;
   uint32_t* d_op_of_tensor = nullptr;
   uint32_t* d_slot_of_op = nullptr;
   uint32_t* d_tensor_tile_start = nullptr;  // n_tensors + 1
+  uint32_t* d_active_tile_start = nullptr;  // n_tensors + 1, rewritten by every replay step
   moev::ScanJob* d_jobs = nullptr;
   uint32_t* d_status = nullptr;
   void** d_state_ptrs = nullptr;            // [4 * n_tensors]
@@ -82,7 +92,7 @@ struct moev_plan {
   bool state_valid = false, grad_valid = false;
   StageSlot ring[kRing];
   int ring_next = 0;
-  std::vector<uint32_t> slot_tiles;         // host-side tile counts (grid sizing only)
+  std::vector<uint32_t> slot_tiles, slot_tiles_unpack;  // host-side tile counts (grid sizing only)
   uint32_t tensor_tiles = 0;
 
   ~moev_plan() {
@@ -116,14 +126,19 @@ uint32_t tiles_of(uint64_t padded, uint64_t tile) { return static_cast<uint32_t>
 void compute_host_tiles(moev_plan* pl) {
   const auto& h = pl->host;
   pl->slot_tiles.assign(h.window, 0);
+  pl->slot_tiles_unpack.assign(h.window, 0);
   for (uint32_t k = 0; k < h.window; ++k) {
-    uint64_t n = 0;
-    for (uint32_t j = 0; j < h.slots[k].n_segments; ++j)
-      n += tiles_of(round_up(h.segments[h.slots[k].first_segment + j].nbytes, h.align), pl->copy_tile_bytes);
+    uint64_t n = 0, nu = 0;
+    for (uint32_t j = 0; j < h.slots[k].n_segments; ++j) {
+      const uint64_t padded = round_up(h.segments[h.slots[k].first_segment + j].nbytes, h.align);
+      n += tiles_of(padded, pl->eff_copy_tile());
+      nu += tiles_of(padded, pl->eff_unpack_tile());
+    }
     pl->slot_tiles[k] = static_cast<uint32_t>(n);
+    pl->slot_tiles_unpack[k] = static_cast<uint32_t>(nu);
   }
   uint64_t n = 0;
-  for (const auto& t : h.tensors) n += tiles_of(t.numel, pl->adam_tile_elems);
+  for (const auto& t : h.tensors) n += tiles_of(t.numel, pl->eff_adam_tile());
   pl->tensor_tiles = static_cast<uint32_t>(n);
 }
 
@@ -145,12 +160,14 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
   const size_t o_numel = carve(h.n_tensors * sizeof(uint64_t));
   const size_t o_opt = carve(h.n_tensors * sizeof(uint32_t));
   const size_t o_slot = carve(h.n_ops * sizeof(uint32_t));
-  const size_t o_jobs = carve((h.window + 1) * sizeof(moev::ScanJob));
+  const size_t o_jobs = carve((2 * h.window + 1) * sizeof(moev::ScanJob));
   const size_t input_bytes = off;
   const size_t o_dst = carve(n_seg * sizeof(uint64_t));
   const size_t o_tile = carve((n_seg + h.window) * sizeof(uint32_t));
+  const size_t o_utile = carve((n_seg + h.window) * sizeof(uint32_t));
   const size_t o_total = carve(h.window * sizeof(uint64_t));
   const size_t o_ttile = carve((h.n_tensors + 1) * sizeof(uint32_t));
+  const size_t o_atile = carve((h.n_tensors + 1) * sizeof(uint32_t));
   const size_t o_status = carve(sizeof(uint32_t));
   pl->device = dev;  // from here on the destructor releases whatever was allocated
   MOEV_HIP(hipMalloc(reinterpret_cast<void**>(&pl->d_tables), off));
@@ -169,8 +186,10 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
   pl->d_jobs = reinterpret_cast<moev::ScanJob*>(d + o_jobs);
   pl->d_dst_off = reinterpret_cast<uint64_t*>(d + o_dst);
   pl->d_seg_tile_start = reinterpret_cast<uint32_t*>(d + o_tile);
+  pl->d_seg_tile_start_unpack = reinterpret_cast<uint32_t*>(d + o_utile);
   pl->d_slot_total = reinterpret_cast<uint64_t*>(d + o_total);
   pl->d_tensor_tile_start = reinterpret_cast<uint32_t*>(d + o_ttile);
+  pl->d_active_tile_start = reinterpret_cast<uint32_t*>(d + o_atile);
   pl->d_status = reinterpret_cast<uint32_t*>(d + o_status);
 
   char* m = static_cast<char*>(pl->pinned_tables);
@@ -217,15 +236,23 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
                             pl->d_slot_total + k,
                             round_up(MOEV_HEADER_BYTES, h.align),
                             h.align,
-                            static_cast<uint64_t>(pl->copy_tile_bytes),
+                            pl->eff_copy_tile(),
                             h.slots[k].n_segments,
                             static_cast<uint32_t>(sizeof(moev::SegDesc) / sizeof(uint64_t))};
   }
-  jobs[h.window] = moev::ScanJob{pl->d_numel, nullptr, pl->d_tensor_tile_start, nullptr, 0, 1,
-                                 static_cast<uint64_t>(pl->adam_tile_elems), h.n_tensors, 1};
-  const size_t input_bytes = jobs_at + (h.window + 1) * sizeof(moev::ScanJob);
+  // the unpack may use another tile size: same offsets (not written again), its own tile map
+  for (uint32_t k = 0; k < h.window; ++k) {
+    jobs[h.window + k] = jobs[k];
+    jobs[h.window + k].prefix_out = nullptr;
+    jobs[h.window + k].total_out = nullptr;
+    jobs[h.window + k].tile_start_out = pl->d_seg_tile_start_unpack + h.slots[k].first_segment + k;
+    jobs[h.window + k].tile = pl->eff_unpack_tile();
+  }
+  jobs[2 * h.window] = moev::ScanJob{pl->d_numel, nullptr, pl->d_tensor_tile_start, nullptr, 0, 1,
+                                     pl->eff_adam_tile(), h.n_tensors, 1};
+  const size_t input_bytes = jobs_at + (2 * h.window + 1) * sizeof(moev::ScanJob);
   MOEV_HIP(hipMemcpyAsync(pl->d_tables, pl->pinned_tables, input_bytes, hipMemcpyHostToDevice, s));
-  MOEV_HIP(moev::launch_layout_scan(pl->d_jobs, h.window + 1, s));
+  MOEV_HIP(moev::launch_layout_scan(pl->d_jobs, 2 * h.window + 1, s));
   compute_host_tiles(pl);
   pl->uploaded = true;
   return MOEV_OK;
@@ -283,21 +310,21 @@ void fill_header(const moev_plan* pl, uint32_t slot, uint64_t iter, uint64_t out
   out[6] = h.align;
 }
 
-moev::CopyArgs copy_args(const moev_plan* pl, uint32_t slot, uint64_t iter, void* d_packed) {
+moev::CopyArgs copy_args(const moev_plan* pl, uint32_t slot, uint64_t iter, void* d_packed, bool unpack) {
   const auto& h = pl->host;
   const uint32_t first = h.slots[slot].first_segment;
   moev::CopyArgs a{};
   a.segs = pl->d_segs + first;
   a.dst_off = pl->d_dst_off + first;
-  a.tile_start = pl->d_seg_tile_start + first + slot;
+  a.tile_start = (unpack ? pl->d_seg_tile_start_unpack : pl->d_seg_tile_start) + first + slot;
   a.ptrs = pl->d_state_ptrs;
   a.packed = static_cast<uint8_t*>(d_packed);
   fill_header(pl, slot, iter, a.header);
   a.n_seg = h.slots[slot].n_segments;
   a.n_tensors = h.n_tensors;
-  a.tile_bytes = static_cast<uint32_t>(pl->copy_tile_bytes);
+  a.tile_bytes = static_cast<uint32_t>(unpack ? pl->eff_unpack_tile() : pl->eff_copy_tile());
   a.align = h.align;
-  a.lds_entries = a.n_seg + 1 <= moev::kMaxLdsEntries ? a.n_seg + 1 : 0;
+  a.lds_entries = (pl->persistent && a.n_seg + 1 <= moev::kMaxLdsEntries) ? a.n_seg + 1 : 0;
   a.slot = slot;
   a.n_ops = h.n_ops;
   a.slot_of_op = pl->d_slot_of_op;
@@ -448,12 +475,10 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
     case MOEV_TUNE_COPY_TILE_BYTES:
       if (value < 4096 || value % 4096 || value > (1 << 26)) return fail(MOEV_E_INVAL, "copy tile must be a multiple of 4096 in [4096, 64 MiB]");
       p->copy_tile_bytes = value;
-      p->uploaded = false;  // tile tables are rebuilt by the next GPU call
       break;
     case MOEV_TUNE_ADAM_TILE_ELEMS:
       if (value < 1024 || value % 1024 || value > (1 << 24)) return fail(MOEV_E_INVAL, "adam tile must be a multiple of 1024 in [1024, 16 Mi]");
       p->adam_tile_elems = value;
-      p->uploaded = false;
       break;
     case MOEV_TUNE_COPY_MAX_BLOCKS:
       if (value < 0 || value > (1 << 20)) return fail(MOEV_E_INVAL, "block cap out of range");
@@ -466,9 +491,43 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
     case MOEV_TUNE_NONTEMPORAL:
       p->nontemporal = value ? 1 : 0;
       break;
+    case MOEV_TUNE_PERSISTENT:
+      p->persistent = value ? 1 : 0;
+      break;
+    case MOEV_TUNE_COPY_THREADS:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->copy_unroll)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->copy_threads = value;
+      break;
+    case MOEV_TUNE_COPY_UNROLL:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(p->copy_threads), static_cast<uint32_t>(value)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->copy_unroll = value;
+      break;
+    case MOEV_TUNE_UNPACK_THREADS:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->unpack_unroll)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->unpack_threads = value;
+      break;
+    case MOEV_TUNE_UNPACK_UNROLL:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(p->unpack_threads), static_cast<uint32_t>(value)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->unpack_unroll = value;
+      break;
+    case MOEV_TUNE_ADAM_THREADS:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->adam_unroll)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->adam_threads = value;
+      break;
+    case MOEV_TUNE_ADAM_UNROLL:
+      if (!moev::direct_shape_supported(static_cast<uint32_t>(p->adam_threads), static_cast<uint32_t>(value)))
+        return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
+      p->adam_unroll = value;
+      break;
     default:
       return fail(MOEV_E_INVAL, "moev_tune: unknown knob %d", knob);
   }
+  p->uploaded = false;  // the tile tables are rebuilt by the next GPU call
   compute_host_tiles(p);
   return MOEV_OK;
 }
@@ -481,6 +540,13 @@ int64_t moev_tune_get(const moev_plan* p, int knob) {
     case MOEV_TUNE_ADAM_TILE_ELEMS: return p->adam_tile_elems;
     case MOEV_TUNE_ADAM_MAX_BLOCKS: return p->adam_max_blocks;
     case MOEV_TUNE_NONTEMPORAL: return p->nontemporal;
+    case MOEV_TUNE_PERSISTENT: return p->persistent;
+    case MOEV_TUNE_COPY_THREADS: return p->copy_threads;
+    case MOEV_TUNE_COPY_UNROLL: return p->copy_unroll;
+    case MOEV_TUNE_UNPACK_THREADS: return p->unpack_threads;
+    case MOEV_TUNE_UNPACK_UNROLL: return p->unpack_unroll;
+    case MOEV_TUNE_ADAM_THREADS: return p->adam_threads;
+    case MOEV_TUNE_ADAM_UNROLL: return p->adam_unroll;
     default: return -1;
   }
 }
@@ -529,6 +595,24 @@ int ckpt_plan_device_status(moev_plan* p, void* stream) {
   return MOEV_OK;
 }
 
+int moev_copy_probe(void* d_dst, const void* d_src, size_t nbytes, uint32_t blocks, int nontemporal, void* stream) {
+  // blocks == 0: one 4 KB tile per workgroup (the default gather shape); otherwise a fixed grid, 32 KB per step
+  if (!d_dst || !d_src || nbytes == 0 || (nbytes & 15u)) return fail(MOEV_E_INVAL, "moev_copy_probe: null pointer or size not a multiple of 16");
+  if (!aligned16(d_dst) || !aligned16(d_src)) return fail(MOEV_E_INVAL, "moev_copy_probe: pointers must be 16-byte aligned");
+  uint32_t unroll = 8;
+  if (blocks == 0) {
+    unroll = 1;
+    const uint64_t tiles = (nbytes + 4095) / 4096;
+    if (tiles >= (1ull << 31)) return fail(MOEV_E_RANGE, "moev_copy_probe: too large");
+    blocks = static_cast<uint32_t>(tiles);
+  } else {
+    const uint64_t chunks = (nbytes + 32767) / 32768;
+    if (blocks > chunks) blocks = static_cast<uint32_t>(chunks);
+  }
+  MOEV_HIP(moev::launch_copy_probe(d_src, d_dst, nbytes, blocks, unroll, nontemporal != 0, static_cast<hipStream_t>(stream)));
+  return MOEV_OK;
+}
+
 int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* state, void* d_packed, size_t cap,
                   void* stream) {
   if (!p || !d_packed) return fail(MOEV_E_INVAL, "snapshot_pack: null argument");
@@ -547,8 +631,12 @@ int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* 
   if (rc != MOEV_OK) return rc;
   rc = bind_state(p, state, s);
   if (rc != MOEV_OK) return rc;
-  const moev::CopyArgs a = copy_args(p, slot, iter, d_packed);
-  MOEV_HIP(moev::launch_pack(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  const moev::CopyArgs a = copy_args(p, slot, iter, d_packed, false);
+  if (p->persistent)
+    MOEV_HIP(moev::launch_pack_persistent(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  else
+    MOEV_HIP(moev::launch_pack_direct(a, p->slot_tiles[slot] ? p->slot_tiles[slot] : 1u, static_cast<uint32_t>(p->copy_threads),
+                                      static_cast<uint32_t>(p->copy_unroll), p->nontemporal != 0, s));
   return MOEV_OK;
 }
 
@@ -611,10 +699,15 @@ int restore_unpack(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_pa
   if (rc != MOEV_OK) return rc;
   if (h_pinned)
     MOEV_HIP(hipMemcpyAsync(d_packed, h_pinned, h.slots[slot].packed_bytes, hipMemcpyHostToDevice, s));
-  moev::CopyArgs a = copy_args(p, slot, 0, d_packed);
+  moev::CopyArgs a = copy_args(p, slot, 0, d_packed, true);
   a.mask = d_active_mask;
   a.derive_compute = derive ? 1u : 0u;
-  MOEV_HIP(moev::launch_unpack(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  if (p->persistent)
+    MOEV_HIP(moev::launch_unpack_persistent(a, grid_for(p, p->slot_tiles_unpack[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  else
+    MOEV_HIP(moev::launch_unpack_direct(a, p->slot_tiles_unpack[slot] ? p->slot_tiles_unpack[slot] : 1u,
+                                        static_cast<uint32_t>(p->unpack_threads), static_cast<uint32_t>(p->unpack_unroll),
+                                        p->nontemporal != 0, s));
   return MOEV_OK;
 }
 
@@ -654,8 +747,8 @@ int convert_replay(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_
   a.grads = p->d_grad_ptrs;
   a.status = p->d_status;
   a.n_tensors = h.n_tensors;
-  a.tile_elems = static_cast<uint32_t>(p->adam_tile_elems);
-  a.lds_entries = h.n_tensors + 1 <= moev::kMaxLdsEntries ? h.n_tensors + 1 : 0;
+  a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
+  a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
   a.lr = adam->lr;
   a.beta1 = adam->beta1;
   a.beta2 = adam->beta2;
@@ -667,7 +760,20 @@ int convert_replay(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_
   a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
   a.decay = adam->lr * adam->weight_decay;
   a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
-  MOEV_HIP(moev::launch_adam(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
+  if (p->persistent) {
+    MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
+  } else {
+    // The device compacts the tile list to the tensors that are active (mask) and have gradients;
+    // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles.
+    uint64_t bound = 0;
+    for (uint32_t t = 0; t < h.n_tensors; ++t)
+      if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
+    if (bound == 0) bound = 1;
+    MOEV_HIP(moev::launch_active_scan(a, p->d_active_tile_start, s));
+    a.tile_start = p->d_active_tile_start;
+    MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
+                                      static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
+  }
   return MOEV_OK;
 }
 

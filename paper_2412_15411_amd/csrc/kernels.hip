@@ -3,18 +3,25 @@
 //   k_layout_scan  packed-snapshot layout of a slot: exclusive prefix sums of the aligned
 //                  segment sizes (segment offsets) and of the per-segment tile counts
 //                  (tile -> segment map), wavefront-level scans combined through LDS.
-//   k_pack         Sec. 3.2 sparse snapshot: gather of per-operator segments into one
-//                  contiguous buffer.  Persistent workgroups walk the tile list; the
-//                  tile -> segment table is staged in LDS; 128-bit streaming loads/stores.
-//   k_unpack       Sec. 3.3 snapshot load: the inverse scatter, fused with the
+//   k_pack_*       Sec. 3.2 sparse snapshot: gather of per-operator segments into one
+//                  contiguous buffer, 128-bit streaming loads/stores.
+//   k_unpack_*     Sec. 3.3 snapshot load: the inverse scatter, fused with the
 //                  master -> bf16 compute-weight refresh of newly active operators and the
 //                  active/frozen mask update.
-//   k_adam         Sec. 3.3 replay: fused multi-tensor Adam step over the active operators
+//   k_active_scan  compacts the tile list of a replay step to the active operators
+//                  (wavefront prefix sum over the per-tensor tile counts).
+//   k_adam_*       Sec. 3.3 replay: fused multi-tensor Adam step over the active operators
 //                  (plain FP32 VALU work; nothing here is a contraction, so no MFMA).
 //
-// All four are bandwidth kernels: zero reuse, so the design goal is many independent
-// 16-byte accesses in flight per lane, full-wave coalescing, and an even spread of tiles over
-// all compute units whatever the segment sizes are.
+// All of these are bandwidth kernels with zero reuse.  Two launch shapes exist for each:
+//   *_direct      one small tile (4-16 KB of each stream) per workgroup, grid = number of
+//                 tiles; the tile -> segment map is searched with scalar loads (the table is a
+//                 few KB and stays in the scalar/L2 caches).  The hardware dispatcher then
+//                 keeps the chip-wide window of in-flight addresses small, contiguous and
+//                 moving linearly, which is what HBM rewards (fewest DRAM row conflicts).
+//   *_persistent  a fixed grid of workgroups walks the tile list with a stride; the map is
+//                 staged in LDS once per workgroup.  Useful when compute units must be left
+//                 to a concurrent kernel (the grid is the knob); slower when alone.
 #include "kernels.hpp"
 
 namespace moev {
@@ -25,18 +32,23 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr uint32_t kVec = 16;                       // bytes per lane access
-constexpr uint32_t kRow = kThreads * kVec;          // bytes one workgroup moves per access wave
+constexpr uint32_t kVec = 16;  // bytes per lane access
+
+// Tensor pointers come out of pointer tables in memory, so the compiler cannot know their
+// address space and would emit flat accesses; every such pointer is device (global) memory.
+#define MOEV_GLOBAL __attribute__((address_space(1)))
 
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T* p) {
-  if constexpr (NT) return __builtin_nontemporal_load(p);
-  else return *p;
+  const MOEV_GLOBAL T* g = (const MOEV_GLOBAL T*)(p);
+  if constexpr (NT) return __builtin_nontemporal_load(g);
+  else return *g;
 }
 template <bool NT, typename T>
 __device__ __forceinline__ void st(T* p, T v) {
-  if constexpr (NT) __builtin_nontemporal_store(v, p);
-  else *p = v;
+  MOEV_GLOBAL T* g = (MOEV_GLOBAL T*)(p);
+  if constexpr (NT) __builtin_nontemporal_store(v, g);
+  else *g = v;
 }
 
 __device__ __forceinline__ uint64_t round_up64(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -62,7 +74,7 @@ __device__ __forceinline__ uint32_t bf16_bits(float x) {
 }
 
 // ------------------------------------------------------------------------------------
-// layout scan
+// prefix sums
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t x) {
   const uint32_t lane = threadIdx.x & 63u;
@@ -74,10 +86,27 @@ __device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t x) {
   return x;
 }
 
+// Exclusive scan of one value per thread across a 256-thread workgroup; also returns the
+// workgroup total.  `lds` holds one slot per wavefront.
+__device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t x, uint64_t* lds, uint64_t* total) {
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint64_t incl = wave_inclusive_scan(x);
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  uint64_t before = 0, all = 0;
+#pragma unroll
+  for (uint32_t w = 0; w < kThreads / 64; ++w) {
+    if (w < wave) before += lds[w];
+    all += lds[w];
+  }
+  __syncthreads();
+  *total = all;
+  return before + incl - x;
+}
+
 __global__ __launch_bounds__(kThreads) void k_layout_scan(const ScanJob* __restrict__ jobs) {
   const ScanJob job = jobs[blockIdx.x];
-  __shared__ uint64_t wave_total[2][kThreads / 64];
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  __shared__ uint64_t lds_bytes[kThreads / 64], lds_tiles[kThreads / 64];
   uint64_t carry_bytes = job.first, carry_tiles = 0;
   for (uint32_t base = 0; base < job.n; base += kThreads) {
     const uint32_t i = base + threadIdx.x;
@@ -86,30 +115,15 @@ __global__ __launch_bounds__(kThreads) void k_layout_scan(const ScanJob* __restr
       padded = round_up64(job.sizes[static_cast<uint64_t>(i) * job.stride], job.gran);
       tiles = (padded + job.tile - 1) / job.tile;
     }
-    const uint64_t incl_bytes = wave_inclusive_scan(padded);
-    const uint64_t incl_tiles = wave_inclusive_scan(tiles);
-    if (lane == 63) {
-      wave_total[0][wave] = incl_bytes;
-      wave_total[1][wave] = incl_tiles;
-    }
-    __syncthreads();
-    uint64_t before_bytes = carry_bytes, before_tiles = carry_tiles, all_bytes = 0, all_tiles = 0;
-#pragma unroll
-    for (uint32_t w = 0; w < kThreads / 64; ++w) {
-      if (w < wave) {
-        before_bytes += wave_total[0][w];
-        before_tiles += wave_total[1][w];
-      }
-      all_bytes += wave_total[0][w];
-      all_tiles += wave_total[1][w];
-    }
+    uint64_t all_bytes, all_tiles;
+    const uint64_t excl_bytes = block_exclusive_scan(padded, lds_bytes, &all_bytes);
+    const uint64_t excl_tiles = block_exclusive_scan(tiles, lds_tiles, &all_tiles);
     if (i < job.n) {
-      if (job.prefix_out) job.prefix_out[i] = before_bytes + incl_bytes - padded;
-      job.tile_start_out[i] = static_cast<uint32_t>(before_tiles + incl_tiles - tiles);
+      if (job.prefix_out) job.prefix_out[i] = carry_bytes + excl_bytes;
+      job.tile_start_out[i] = static_cast<uint32_t>(carry_tiles + excl_tiles);
     }
     carry_bytes += all_bytes;
     carry_tiles += all_tiles;
-    __syncthreads();
   }
   if (threadIdx.x == 0) {
     job.tile_start_out[job.n] = static_cast<uint32_t>(carry_tiles);
@@ -117,10 +131,33 @@ __global__ __launch_bounds__(kThreads) void k_layout_scan(const ScanJob* __restr
   }
 }
 
+// Tile list of one replay step: a tensor contributes its tiles only if its operator is active
+// and it has gradients.  out[t] = first compacted tile of tensor t, out[n] = number of tiles.
+__global__ __launch_bounds__(kThreads) void k_active_scan(const AdamArgs a, uint32_t* __restrict__ out) {
+  // (not hot: one workgroup per replay step)
+  __shared__ uint64_t lds[kThreads / 64];
+  uint64_t carry = 0;
+  for (uint32_t base = 0; base < a.n_tensors; base += kThreads) {
+    const uint32_t t = base + threadIdx.x;
+    uint64_t tiles = 0;
+    if (t < a.n_tensors) {
+      const uint64_t numel = a.numel[t];
+      const bool active = a.mask[a.op_of_tensor[t]] != 0;
+      const bool has_grad = a.grads[t] != nullptr;
+      if (active && !has_grad && numel) *a.status = 2u;  // reported by the status query, tensor skipped
+      if (active && has_grad) tiles = (numel + a.tile_elems - 1) / a.tile_elems;
+    }
+    uint64_t all;
+    const uint64_t excl = block_exclusive_scan(tiles, lds, &all);
+    if (t < a.n_tensors) out[t] = static_cast<uint32_t>(carry + excl);
+    carry += all;
+  }
+  if (threadIdx.x == 0) out[a.n_tensors] = static_cast<uint32_t>(carry);
+}
+
 // ------------------------------------------------------------------------------------
-// pack (gather) and unpack (scatter)
+// pack (gather) and unpack (scatter): byte range [begin, end) of one segment
 // ------------------------------------------------------------------------------------
-constexpr uint32_t kCopyUnroll = 8;  // 16-byte accesses in flight per lane
 
 // 16 bytes of a dense tensor at byte offset `o`; bytes at or beyond `nbytes` read as zero.
 template <bool NT>
@@ -130,157 +167,217 @@ __device__ __forceinline__ u32x4 load_dense(const uint8_t* __restrict__ src, uin
   if (o < nbytes) {
     const uint32_t left = static_cast<uint32_t>(nbytes - o);
     uint32_t w[4] = {0u, 0u, 0u, 0u};
-    for (uint32_t b = 0; b < left; ++b) w[b >> 2] |= static_cast<uint32_t>(src[o + b]) << (8 * (b & 3));
+    for (uint32_t b = 0; b < left; ++b) w[b >> 2] |= static_cast<uint32_t>(ld<false>(src + o + b)) << (8 * (b & 3));
     r = u32x4{w[0], w[1], w[2], w[3]};
   }
   return r;
 }
 
-// Stages the tile_start table into LDS (if it fits) and returns the table to search.
-__device__ __forceinline__ const uint32_t* stage_table(const uint32_t* __restrict__ global_table,
-                                                       uint32_t lds_entries, uint32_t* lds) {
-  if (lds_entries == 0) return global_table;
-  for (uint32_t i = threadIdx.x; i < lds_entries; i += kThreads) lds[i] = global_table[i];
-  __syncthreads();
-  return nullptr;  // caller uses the LDS copy
-}
-
-template <bool NT>
-__global__ __launch_bounds__(kThreads) void k_pack(const CopyArgs a) {
-  extern __shared__ uint32_t lds_start[];
-  const uint32_t tid = threadIdx.x;
-  const bool in_global = stage_table(a.tile_start, a.lds_entries, lds_start) != nullptr;
-  const uint32_t n_tiles = a.tile_start[a.n_seg];
-
-  if (blockIdx.x == 0) {
-    // header (32 eight-byte words) and, for alignments above 256, the gap before the first segment
-    if (tid < 32) {
-      uint64_t w = 0;
+// dst[begin, end) = src[begin, end) with zeros beyond nbytes; end is a multiple of 16 within
+// the segment's padded size.  T threads, U independent accesses in flight per lane.
+template <uint32_t T, uint32_t U, bool NT>
+__device__ __forceinline__ void pack_range(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                           uint64_t begin, uint64_t end, uint64_t nbytes) {
+  constexpr uint64_t kRow = static_cast<uint64_t>(T) * kVec;
+  for (uint64_t base = begin + static_cast<uint64_t>(threadIdx.x) * kVec; base < end; base += kRow * U) {
+    u32x4 r[U];
 #pragma unroll
-      for (uint32_t k = 0; k < 7; ++k)
-        if (tid == k) w = a.header[k];
-      reinterpret_cast<uint64_t*>(a.packed)[tid] = w;
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t o = base + u * kRow;
+      if (o < end) r[u] = load_dense<NT>(src, o, nbytes);
     }
-    const uint64_t first = round_up64(256, a.align);
-    for (uint64_t o = 256 + static_cast<uint64_t>(tid) * kVec; o < first; o += kRow)
-      *reinterpret_cast<u32x4*>(a.packed + o) = u32x4{0u, 0u, 0u, 0u};
-  }
-
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const uint32_t j = in_global ? owner_of_tile(a.tile_start, a.n_seg, tile)
-                                 : owner_of_tile(lds_start, a.n_seg, tile);
-    const uint32_t local = tile - (in_global ? a.tile_start[j] : lds_start[j]);
-    const SegDesc seg = a.segs[j];
-    const uint8_t* __restrict__ src =
-        static_cast<const uint8_t*>(a.ptrs[static_cast<uint64_t>(seg.kind) * a.n_tensors + seg.tensor]);
-    uint8_t* __restrict__ dst = a.packed + a.dst_off[j];
-    const uint64_t padded = round_up64(seg.nbytes, a.align);
-    const uint64_t begin = static_cast<uint64_t>(local) * a.tile_bytes;
-    const uint64_t end = begin + a.tile_bytes < padded ? begin + a.tile_bytes : padded;
-
-    for (uint64_t base = begin + static_cast<uint64_t>(tid) * kVec; base < end; base += kRow * kCopyUnroll) {
-      u32x4 r[kCopyUnroll];
 #pragma unroll
-      for (uint32_t u = 0; u < kCopyUnroll; ++u) {
-        const uint64_t o = base + static_cast<uint64_t>(u) * kRow;
-        if (o < end) r[u] = load_dense<NT>(src, o, seg.nbytes);
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < kCopyUnroll; ++u) {
-        const uint64_t o = base + static_cast<uint64_t>(u) * kRow;
-        if (o < end) st<NT>(reinterpret_cast<u32x4*>(dst + o), r[u]);
-      }
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t o = base + u * kRow;
+      if (o < end) st<NT>(reinterpret_cast<u32x4*>(dst + o), r[u]);
     }
   }
 }
 
-template <bool NT>
-__global__ __launch_bounds__(kThreads) void k_unpack(const CopyArgs a) {
-  extern __shared__ uint32_t lds_start[];
-  __shared__ uint32_t header_ok;
-  const uint32_t tid = threadIdx.x;
+// dst[begin, end) = src[begin, end), end <= nbytes (padding is never written back); for master
+// segments of newly active operators `comp` also receives the bf16 cast of every value.
+template <uint32_t T, uint32_t U, bool NT>
+__device__ __forceinline__ void unpack_range(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                             uint8_t* __restrict__ comp, uint64_t begin, uint64_t end,
+                                             uint64_t nbytes) {
+  constexpr uint64_t kRow = static_cast<uint64_t>(T) * kVec;
+  for (uint64_t base = begin + static_cast<uint64_t>(threadIdx.x) * kVec; base < end; base += kRow * U) {
+    u32x4 r[U];
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t o = base + u * kRow;
+      if (o < end) r[u] = ld<NT>(reinterpret_cast<const u32x4*>(src + o));  // padded: always 16 readable bytes
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t o = base + u * kRow;
+      if (o >= end) continue;
+      if (o + kVec <= nbytes) {
+        st<NT>(reinterpret_cast<u32x4*>(dst + o), r[u]);
+        if (comp) {
+          const u32x2 c = {bf16_bits(__uint_as_float(r[u].x)) | (bf16_bits(__uint_as_float(r[u].y)) << 16),
+                           bf16_bits(__uint_as_float(r[u].z)) | (bf16_bits(__uint_as_float(r[u].w)) << 16)};
+          st<NT>(reinterpret_cast<u32x2*>(comp + (o >> 1)), c);
+        }
+      } else {
+        const uint32_t left = static_cast<uint32_t>(nbytes - o);
+        const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+        for (uint32_t b = 0; b < left; ++b) st<false>(dst + o + b, static_cast<uint8_t>(w[b >> 2] >> (8 * (b & 3))));
+        if (comp)
+          for (uint32_t e = 0; e < left / 4; ++e)
+            st<false>(reinterpret_cast<uint16_t*>(comp + (o >> 1)) + e, static_cast<uint16_t>(bf16_bits(__uint_as_float(w[e]))));
+      }
+    }
+  }
+}
 
-  // Refuse a snapshot that does not belong to this plan and slot: nothing is scattered.
-  if (tid == 0) {
-    const uint64_t* h = reinterpret_cast<const uint64_t*>(a.packed);
-    uint32_t ok = 1;
+// header (32 eight-byte words) and, for alignments above 256, the zero gap before the first segment
+template <uint32_t T>
+__device__ __forceinline__ void write_header(const CopyArgs& a) {
+  const uint32_t tid = threadIdx.x;
+  if (tid < 32) {
+    uint64_t w = 0;
 #pragma unroll
     for (uint32_t k = 0; k < 7; ++k)
-      if (k != 3 && h[k] != a.header[k]) ok = 0;  // word 3 is the iteration: any value is fine
-    header_ok = ok;
-    if (!ok && blockIdx.x == 0) *a.status = 1u;
+      if (tid == k) w = a.header[k];
+    reinterpret_cast<uint64_t*>(a.packed)[tid] = w;
   }
+  const uint64_t first = a.align > 256 ? a.align : 256;  // roundup(256, align) for a power of two
+  for (uint64_t o = 256 + static_cast<uint64_t>(tid) * kVec; o < first; o += static_cast<uint64_t>(T) * kVec)
+    *reinterpret_cast<u32x4*>(a.packed + o) = u32x4{0u, 0u, 0u, 0u};
+}
+
+// A snapshot that does not belong to this plan and slot is refused: nothing is scattered.
+// (word 3 is the iteration: any value is fine.)  Uniform across the workgroup.
+__device__ __forceinline__ bool header_matches(const CopyArgs& a, const uint64_t* __restrict__ h) {
+  bool ok = true;
+#pragma unroll
+  for (uint32_t k = 0; k < 7; ++k)
+    if (k != 3 && h[k] != a.header[k]) ok = false;
+  return ok;
+}
+
+// operator state machine: the slot's operators become active, later ones are frozen
+template <uint32_t T>
+__device__ __forceinline__ void update_mask(const CopyArgs& a) {
+  if (!a.mask) return;
+  for (uint32_t e = threadIdx.x; e < a.n_ops; e += T) {
+    const uint32_t s = a.slot_of_op[e];
+    if (s == a.slot) a.mask[e] = 1;
+    else if (s > a.slot) a.mask[e] = 0;
+  }
+}
+
+// Read-only tables of a copy launch.  They are separate `const __restrict__` kernel parameters
+// (not members of the by-value argument block) so that the compiler may fetch them with scalar
+// loads: every lookup is uniform across the workgroup.
+#define MOEV_COPY_TABLES                                                                        \
+  const uint32_t *__restrict__ tile_start, const SegDesc *__restrict__ segs,                    \
+      const uint64_t *__restrict__ dst_off, void *const *__restrict__ ptrs
+#define MOEV_COPY_TABLE_ARGS tile_start, segs, dst_off, ptrs
+
+template <uint32_t T, uint32_t U, bool NT, typename Table>
+__device__ __forceinline__ void pack_tile(const CopyArgs& a, Table start, const SegDesc* __restrict__ segs,
+                                          const uint64_t* __restrict__ dst_off, void* const* __restrict__ ptrs,
+                                          uint32_t tile) {
+  const uint32_t j = owner_of_tile(start, a.n_seg, tile);
+  const uint32_t local = tile - start[j];
+  const SegDesc seg = segs[j];
+  const uint8_t* src = static_cast<const uint8_t*>(ptrs[static_cast<uint64_t>(seg.kind) * a.n_tensors + seg.tensor]);
+  uint8_t* dst = a.packed + dst_off[j];
+  const uint64_t padded = (seg.nbytes + a.align - 1) & ~static_cast<uint64_t>(a.align - 1);  // align is a power of two
+  const uint64_t begin = static_cast<uint64_t>(local) * a.tile_bytes;
+  const uint64_t end = begin + a.tile_bytes < padded ? begin + a.tile_bytes : padded;
+  pack_range<T, U, NT>(src, dst, begin, end, seg.nbytes);
+}
+
+template <uint32_t T, uint32_t U, bool NT, typename Table>
+__device__ __forceinline__ void unpack_tile(const CopyArgs& a, Table start, const SegDesc* __restrict__ segs,
+                                            const uint64_t* __restrict__ dst_off, void* const* __restrict__ ptrs,
+                                            uint32_t tile) {
+  const uint32_t j = owner_of_tile(start, a.n_seg, tile);
+  const uint32_t local = tile - start[j];
+  const SegDesc seg = segs[j];
+  uint8_t* dst = static_cast<uint8_t*>(ptrs[static_cast<uint64_t>(seg.kind) * a.n_tensors + seg.tensor]);
+  const uint8_t* src = a.packed + dst_off[j];
+  uint8_t* comp = (a.derive_compute && seg.kind == 0u) ? static_cast<uint8_t*>(ptrs[3ull * a.n_tensors + seg.tensor])
+                                                       : nullptr;
+  const uint64_t begin = static_cast<uint64_t>(local) * a.tile_bytes;
+  uint64_t end = begin + a.tile_bytes;
+  if (end > seg.nbytes) end = seg.nbytes;
+  unpack_range<T, U, NT>(src, dst, comp, begin, end, seg.nbytes);
+}
+
+// ---- one tile per workgroup ----
+template <uint32_t T, uint32_t U, bool NT>
+__global__ __launch_bounds__(T) void k_pack_direct(MOEV_COPY_TABLES, const CopyArgs a) {
+  if (blockIdx.x == 0) write_header<T>(a);
+  if (blockIdx.x < tile_start[a.n_seg]) pack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, blockIdx.x);
+}
+
+template <uint32_t T, uint32_t U, bool NT>
+__global__ __launch_bounds__(T) void k_unpack_direct(MOEV_COPY_TABLES, const uint64_t* __restrict__ header,
+                                                     const CopyArgs a) {
+  if (!header_matches(a, header)) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.status = 1u;
+    return;
+  }
+  if (blockIdx.x == 0) update_mask<T>(a);
+  if (blockIdx.x < tile_start[a.n_seg]) unpack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, blockIdx.x);
+}
+
+// ---- fixed grid walking the tile list, map staged in LDS ----
+constexpr uint32_t kPersistentUnroll = 8;
+
+__device__ __forceinline__ bool stage_table(const uint32_t* __restrict__ global_table, uint32_t lds_entries,
+                                            uint32_t* lds) {
+  if (lds_entries == 0) return false;
+  for (uint32_t i = threadIdx.x; i < lds_entries; i += kThreads) lds[i] = global_table[i];
   __syncthreads();
-  if (!header_ok) return;
+  return true;
+}
 
-  const bool in_global = stage_table(a.tile_start, a.lds_entries, lds_start) != nullptr;
-  const uint32_t n_tiles = a.tile_start[a.n_seg];
-
-  if (blockIdx.x == 0 && a.mask) {
-    // operator state machine: the slot's operators become active, later ones are frozen
-    for (uint32_t e = tid; e < a.n_ops; e += kThreads) {
-      const uint32_t s = a.slot_of_op[e];
-      if (s == a.slot) a.mask[e] = 1;
-      else if (s > a.slot) a.mask[e] = 0;
-    }
-  }
-
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_pack_persistent(MOEV_COPY_TABLES, const CopyArgs a) {
+  extern __shared__ uint32_t lds_start[];
+  const bool in_lds = stage_table(tile_start, a.lds_entries, lds_start);
+  const uint32_t n_tiles = tile_start[a.n_seg];
+  if (blockIdx.x == 0) write_header<kThreads>(a);
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const uint32_t j = in_global ? owner_of_tile(a.tile_start, a.n_seg, tile)
-                                 : owner_of_tile(lds_start, a.n_seg, tile);
-    const uint32_t local = tile - (in_global ? a.tile_start[j] : lds_start[j]);
-    const SegDesc seg = a.segs[j];
-    uint8_t* __restrict__ dst =
-        static_cast<uint8_t*>(a.ptrs[static_cast<uint64_t>(seg.kind) * a.n_tensors + seg.tensor]);
-    const uint8_t* __restrict__ src = a.packed + a.dst_off[j];
-    const bool derive = a.derive_compute && seg.kind == 0u;
-    uint8_t* __restrict__ comp =
-        derive ? static_cast<uint8_t*>(a.ptrs[3ull * a.n_tensors + seg.tensor]) : nullptr;
-    const uint64_t begin = static_cast<uint64_t>(local) * a.tile_bytes;
-    uint64_t end = begin + a.tile_bytes;
-    if (end > seg.nbytes) end = seg.nbytes;  // padding is never written back
+    if (in_lds) pack_tile<kThreads, kPersistentUnroll, NT>(a, lds_start, segs, dst_off, ptrs, tile);
+    else pack_tile<kThreads, kPersistentUnroll, NT>(a, tile_start, segs, dst_off, ptrs, tile);
+  }
+}
 
-    for (uint64_t base = begin + static_cast<uint64_t>(tid) * kVec; base < end; base += kRow * kCopyUnroll) {
-      u32x4 r[kCopyUnroll];
-#pragma unroll
-      for (uint32_t u = 0; u < kCopyUnroll; ++u) {
-        const uint64_t o = base + static_cast<uint64_t>(u) * kRow;
-        if (o < end) r[u] = ld<NT>(reinterpret_cast<const u32x4*>(src + o));  // padded: always 16 readable bytes
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < kCopyUnroll; ++u) {
-        const uint64_t o = base + static_cast<uint64_t>(u) * kRow;
-        if (o >= end) continue;
-        if (o + kVec <= seg.nbytes) {
-          st<NT>(reinterpret_cast<u32x4*>(dst + o), r[u]);
-          if (derive) {
-            const u32x2 c = {bf16_bits(__uint_as_float(r[u].x)) | (bf16_bits(__uint_as_float(r[u].y)) << 16),
-                             bf16_bits(__uint_as_float(r[u].z)) | (bf16_bits(__uint_as_float(r[u].w)) << 16)};
-            st<NT>(reinterpret_cast<u32x2*>(comp + (o >> 1)), c);
-          }
-        } else {
-          const uint32_t left = static_cast<uint32_t>(seg.nbytes - o);
-          const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
-          for (uint32_t b = 0; b < left; ++b) dst[o + b] = static_cast<uint8_t>(w[b >> 2] >> (8 * (b & 3)));
-          if (derive)
-            for (uint32_t e = 0; e < left / 4; ++e)
-              reinterpret_cast<uint16_t*>(comp + (o >> 1))[e] =
-                  static_cast<uint16_t>(bf16_bits(__uint_as_float(w[e])));
-        }
-      }
-    }
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_unpack_persistent(MOEV_COPY_TABLES, const uint64_t* __restrict__ header,
+                                                                const CopyArgs a) {
+  extern __shared__ uint32_t lds_start[];
+  if (!header_matches(a, header)) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.status = 1u;
+    return;
+  }
+  const bool in_lds = stage_table(tile_start, a.lds_entries, lds_start);
+  const uint32_t n_tiles = tile_start[a.n_seg];
+  if (blockIdx.x == 0) update_mask<kThreads>(a);
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    if (in_lds) unpack_tile<kThreads, kPersistentUnroll, NT>(a, lds_start, segs, dst_off, ptrs, tile);
+    else unpack_tile<kThreads, kPersistentUnroll, NT>(a, tile_start, segs, dst_off, ptrs, tile);
   }
 }
 
 // ------------------------------------------------------------------------------------
 // fused Adam replay
 // ------------------------------------------------------------------------------------
-constexpr uint32_t kAdamUnroll = 2;  // float4 groups per lane per pass: 8 loads in flight
-
 struct AdamConst {
   float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
   bool has_decay;
 };
+
+__device__ __forceinline__ AdamConst adam_const(const AdamArgs& a) {
+  return AdamConst{a.lr, a.beta1, a.beta2, a.eps, a.one_minus_beta1, a.one_minus_beta2, a.bc1, a.bc2, a.decay,
+                   a.has_decay != 0};
+}
 
 // One element.  Operation order is part of the contract (every product and sum rounded
 // separately; this file is compiled with floating-point contraction off).
@@ -295,82 +392,120 @@ __device__ __forceinline__ void adam_element(float& p, float& m, float& v, float
   p = p - c.lr * (m_hat / denom);
 }
 
-template <bool NT>
-__global__ __launch_bounds__(kThreads) void k_adam(const AdamArgs a) {
-  extern __shared__ uint32_t lds_start[];
-  const uint32_t tid = threadIdx.x;
-  const bool in_global = stage_table(a.tile_start, a.lds_entries, lds_start) != nullptr;
-  const uint32_t n_tiles = a.tile_start[a.n_tensors];
-  const AdamConst c = {a.lr, a.beta1, a.beta2, a.eps, a.one_minus_beta1, a.one_minus_beta2,
-                       a.bc1, a.bc2, a.decay, a.has_decay != 0};
+#define MOEV_ADAM_TABLES                                                                              \
+  const uint32_t *__restrict__ tile_start, const uint64_t *__restrict__ numel_of,                     \
+      const uint32_t *__restrict__ op_of_tensor, const uint8_t *__restrict__ mask,                    \
+      void *const *__restrict__ ptrs, void *const *__restrict__ grads
 
+// Elements [begin, end) of tensor t; begin is a multiple of four.
+template <uint32_t T, uint32_t U, bool NT>
+__device__ __forceinline__ void adam_range(const AdamArgs& a, void* const* __restrict__ ptrs,
+                                           void* const* __restrict__ grads, uint32_t t, uint64_t begin, uint64_t end,
+                                           const AdamConst& c) {
+  float* __restrict__ P = static_cast<float*>(ptrs[t]);
+  float* __restrict__ M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
+  float* __restrict__ V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
+  uint16_t* __restrict__ C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
+  const float* __restrict__ G = static_cast<const float*>(grads[t]);
+  for (uint64_t base = begin + 4ull * threadIdx.x; base < end; base += 4ull * T * U) {
+    f32x4 p[U], m[U], v[U], g[U];
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t i = base + 4ull * T * u;
+      if (i + 4 <= end) {
+        p[u] = ld<NT>(reinterpret_cast<const f32x4*>(P + i));
+        m[u] = ld<NT>(reinterpret_cast<const f32x4*>(M + i));
+        v[u] = ld<NT>(reinterpret_cast<const f32x4*>(V + i));
+        g[u] = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
+      }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < U; ++u) {
+      const uint64_t i = base + 4ull * T * u;
+      if (i + 4 <= end) {
+#pragma unroll
+        for (uint32_t e = 0; e < 4; ++e) {
+          float pe = p[u][e], me = m[u][e], ve = v[u][e];
+          adam_element(pe, me, ve, g[u][e], c);
+          p[u][e] = pe;
+          m[u][e] = me;
+          v[u][e] = ve;
+        }
+        st<NT>(reinterpret_cast<f32x4*>(P + i), p[u]);
+        st<NT>(reinterpret_cast<f32x4*>(M + i), m[u]);
+        st<NT>(reinterpret_cast<f32x4*>(V + i), v[u]);
+        const u32x2 cw = {bf16_bits(p[u].x) | (bf16_bits(p[u].y) << 16), bf16_bits(p[u].z) | (bf16_bits(p[u].w) << 16)};
+        st<NT>(reinterpret_cast<u32x2*>(C + i), cw);
+      } else if (i < end) {
+        // ragged tail of a tensor whose length is not a multiple of four
+        for (uint64_t e = i; e < end; ++e) {
+          float pe = ld<false>(P + e), me = ld<false>(M + e), ve = ld<false>(V + e);
+          adam_element(pe, me, ve, ld<false>(G + e), c);
+          st<false>(P + e, pe);
+          st<false>(M + e, me);
+          st<false>(V + e, ve);
+          st<false>(C + e, static_cast<uint16_t>(bf16_bits(pe)));
+        }
+      }
+    }
+  }
+}
+
+// one tile per workgroup over the compacted tile list written by k_active_scan
+template <uint32_t T, uint32_t U, bool NT>
+__global__ __launch_bounds__(T) void k_adam_direct(MOEV_ADAM_TABLES, const AdamArgs a) {
+  const uint32_t tile = blockIdx.x;
+  if (tile >= tile_start[a.n_tensors]) return;
+  const uint32_t t = owner_of_tile(tile_start, a.n_tensors, tile);
+  const uint64_t numel = numel_of[t];
+  const uint64_t begin = static_cast<uint64_t>(tile - tile_start[t]) * a.tile_elems;
+  const uint64_t end = begin + a.tile_elems < numel ? begin + a.tile_elems : numel;
+  (void)op_of_tensor;
+  (void)mask;
+  adam_range<T, U, NT>(a, ptrs, grads, t, begin, end, adam_const(a));
+}
+
+// fixed grid over the static (all tensors) tile list; frozen tensors are jumped over
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_adam_persistent(MOEV_ADAM_TABLES, const AdamArgs a) {
+  extern __shared__ uint32_t lds_start[];
+  const bool in_lds = stage_table(tile_start, a.lds_entries, lds_start);
+  const uint32_t* start = in_lds ? lds_start : tile_start;  // generic pointer: LDS or global
+  const uint32_t n_tiles = tile_start[a.n_tensors];
+  const AdamConst c = adam_const(a);
   uint32_t tile = blockIdx.x;
   while (tile < n_tiles) {
-    const uint32_t t = in_global ? owner_of_tile(a.tile_start, a.n_tensors, tile)
-                                 : owner_of_tile(lds_start, a.n_tensors, tile);
-    const uint32_t t_first = in_global ? a.tile_start[t] : lds_start[t];
-    const float* __restrict__ G = static_cast<const float*>(a.grads[t]);
-    const bool active = a.mask[a.op_of_tensor[t]] != 0;
-    if (active && !G && tid == 0) *a.status = 2u;  // an active operator without gradients: reported, skipped
-    if (!active || !G) {
-      // frozen operator: jump to this workgroup's first tile at or beyond the next tensor
-      const uint32_t t_end = in_global ? a.tile_start[t + 1] : lds_start[t + 1];
-      const uint32_t skip = (t_end - tile + gridDim.x - 1) / gridDim.x;
-      tile += skip * gridDim.x;
+    const uint32_t t = owner_of_tile(start, a.n_tensors, tile);
+    const bool active = mask[op_of_tensor[t]] != 0;
+    const bool has_grad = grads[t] != nullptr;
+    if (active && !has_grad && threadIdx.x == 0) *a.status = 2u;
+    if (!active || !has_grad) {
+      // jump to this workgroup's first tile at or beyond the next tensor
+      const uint32_t t_end = start[t + 1];
+      tile += (t_end - tile + gridDim.x - 1) / gridDim.x * gridDim.x;
       continue;
     }
-    const uint64_t numel = a.numel[t];
-    float* __restrict__ P = static_cast<float*>(a.ptrs[t]);
-    float* __restrict__ M = static_cast<float*>(a.ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
-    float* __restrict__ V = static_cast<float*>(a.ptrs[2ull * a.n_tensors + t]);
-    uint16_t* __restrict__ C = static_cast<uint16_t*>(a.ptrs[3ull * a.n_tensors + t]);
-    const uint64_t begin = static_cast<uint64_t>(tile - t_first) * a.tile_elems;
+    const uint64_t numel = numel_of[t];
+    const uint64_t begin = static_cast<uint64_t>(tile - start[t]) * a.tile_elems;
     const uint64_t end = begin + a.tile_elems < numel ? begin + a.tile_elems : numel;
-
-    for (uint64_t base = begin + 4ull * tid; base < end; base += 4ull * kThreads * kAdamUnroll) {
-      f32x4 p[kAdamUnroll], m[kAdamUnroll], v[kAdamUnroll], g[kAdamUnroll];
-#pragma unroll
-      for (uint32_t u = 0; u < kAdamUnroll; ++u) {
-        const uint64_t i = base + 4ull * kThreads * u;
-        if (i + 4 <= end) {
-          p[u] = ld<NT>(reinterpret_cast<const f32x4*>(P + i));
-          m[u] = ld<NT>(reinterpret_cast<const f32x4*>(M + i));
-          v[u] = ld<NT>(reinterpret_cast<const f32x4*>(V + i));
-          g[u] = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
-        }
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < kAdamUnroll; ++u) {
-        const uint64_t i = base + 4ull * kThreads * u;
-        if (i + 4 <= end) {
-#pragma unroll
-          for (uint32_t e = 0; e < 4; ++e) {
-            float pe = p[u][e], me = m[u][e], ve = v[u][e];
-            adam_element(pe, me, ve, g[u][e], c);
-            p[u][e] = pe;
-            m[u][e] = me;
-            v[u][e] = ve;
-          }
-          st<NT>(reinterpret_cast<f32x4*>(P + i), p[u]);
-          st<NT>(reinterpret_cast<f32x4*>(M + i), m[u]);
-          st<NT>(reinterpret_cast<f32x4*>(V + i), v[u]);
-          const u32x2 cw = {bf16_bits(p[u].x) | (bf16_bits(p[u].y) << 16),
-                            bf16_bits(p[u].z) | (bf16_bits(p[u].w) << 16)};
-          st<NT>(reinterpret_cast<u32x2*>(C + i), cw);
-        } else if (i < end) {
-          // ragged tail of a tensor whose length is not a multiple of four
-          for (uint64_t e = i; e < end; ++e) {
-            float pe = P[e], me = M[e], ve = V[e];
-            adam_element(pe, me, ve, G[e], c);
-            P[e] = pe;
-            M[e] = me;
-            V[e] = ve;
-            C[e] = static_cast<uint16_t>(bf16_bits(pe));
-          }
-        }
-      }
-    }
+    adam_range<kThreads, 2, NT>(a, ptrs, grads, t, begin, end, c);
     tile += gridDim.x;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// plain contiguous copy: the yardstick for the gather/scatter kernels and the known-size
+// kernel against which the HBM traffic counters are calibrated
+// ------------------------------------------------------------------------------------
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_copy_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                         uint64_t nbytes, uint32_t unroll) {
+  const uint64_t row = static_cast<uint64_t>(kThreads) * kVec;
+  const uint64_t chunk = row * unroll;
+  for (uint64_t begin = blockIdx.x * chunk; begin < nbytes; begin += static_cast<uint64_t>(gridDim.x) * chunk) {
+    const uint64_t end = begin + chunk < nbytes ? begin + chunk : nbytes;
+    if (unroll == 1) pack_range<kThreads, 1, NT>(src, dst, begin, end, nbytes);
+    else pack_range<kThreads, 8, NT>(src, dst, begin, end, nbytes);
   }
 }
 
@@ -385,24 +520,88 @@ hipError_t launch_layout_scan(const ScanJob* d_jobs, uint32_t n_jobs, hipStream_
   return hipGetLastError();
 }
 
-hipError_t launch_pack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s) {
-  const size_t lds = static_cast<size_t>(a.lds_entries) * sizeof(uint32_t);
-  if (nontemporal) hipLaunchKernelGGL(k_pack<true>, dim3(blocks), dim3(kThreads), lds, s, a);
-  else hipLaunchKernelGGL(k_pack<false>, dim3(blocks), dim3(kThreads), lds, s, a);
+hipError_t launch_copy_probe(const void* src, void* dst, uint64_t nbytes, uint32_t blocks, uint32_t unroll,
+                             bool nontemporal, hipStream_t s) {
+  const uint8_t* sp = static_cast<const uint8_t*>(src);
+  uint8_t* dp = static_cast<uint8_t*>(dst);
+  if (nontemporal) hipLaunchKernelGGL(k_copy_probe<true>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, unroll);
+  else hipLaunchKernelGGL(k_copy_probe<false>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, unroll);
   return hipGetLastError();
 }
 
-hipError_t launch_unpack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s) {
-  const size_t lds = static_cast<size_t>(a.lds_entries) * sizeof(uint32_t);
-  if (nontemporal) hipLaunchKernelGGL(k_unpack<true>, dim3(blocks), dim3(kThreads), lds, s, a);
-  else hipLaunchKernelGGL(k_unpack<false>, dim3(blocks), dim3(kThreads), lds, s, a);
+namespace {
+
+// picks the <threads, unroll> instantiation of a one-tile-per-workgroup kernel
+#define MOEV_DIRECT_CASE(KERNEL, TT, UU)                                                              \
+  if (threads == TT && unroll == UU) {                                                                \
+    if (nt) hipLaunchKernelGGL((KERNEL<TT, UU, true>), dim3(blocks), dim3(TT), 0, s, MOEV_LAUNCH_ARGS); \
+    else hipLaunchKernelGGL((KERNEL<TT, UU, false>), dim3(blocks), dim3(TT), 0, s, MOEV_LAUNCH_ARGS);   \
+    return hipGetLastError();                                                                         \
+  }
+
+#define MOEV_DIRECT_ALL(KERNEL)     \
+  MOEV_DIRECT_CASE(KERNEL, 64, 1)   \
+  MOEV_DIRECT_CASE(KERNEL, 128, 1)  \
+  MOEV_DIRECT_CASE(KERNEL, 256, 1)  \
+  MOEV_DIRECT_CASE(KERNEL, 256, 2)  \
+  MOEV_DIRECT_CASE(KERNEL, 256, 4)  \
+  MOEV_DIRECT_CASE(KERNEL, 512, 1)  \
+  MOEV_DIRECT_CASE(KERNEL, 512, 2)  \
+  MOEV_DIRECT_CASE(KERNEL, 1024, 1) \
+  return hipErrorInvalidValue;
+
+}  // namespace
+
+bool direct_shape_supported(uint32_t threads, uint32_t unroll) {
+  return (unroll == 1 && (threads == 64 || threads == 128 || threads == 256 || threads == 512 || threads == 1024)) ||
+         (unroll == 2 && (threads == 256 || threads == 512)) || (unroll == 4 && threads == 256);
+}
+
+#define MOEV_LAUNCH_ARGS a.tile_start, a.segs, a.dst_off, a.ptrs, a
+hipError_t launch_pack_direct(const CopyArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                              hipStream_t s) {
+  MOEV_DIRECT_ALL(k_pack_direct)
+}
+#undef MOEV_LAUNCH_ARGS
+
+#define MOEV_LAUNCH_ARGS a.tile_start, a.segs, a.dst_off, a.ptrs, reinterpret_cast<const uint64_t*>(a.packed), a
+hipError_t launch_unpack_direct(const CopyArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                                hipStream_t s) {
+  MOEV_DIRECT_ALL(k_unpack_direct)
+}
+#undef MOEV_LAUNCH_ARGS
+
+#define MOEV_LAUNCH_ARGS a.tile_start, a.numel, a.op_of_tensor, a.mask, a.ptrs, a.grads, a
+hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                              hipStream_t s) {
+  MOEV_DIRECT_ALL(k_adam_direct)
+}
+#undef MOEV_LAUNCH_ARGS
+
+hipError_t launch_active_scan(const AdamArgs& a, uint32_t* d_out, hipStream_t s) {
+  hipLaunchKernelGGL(k_active_scan, dim3(1), dim3(kThreads), 0, s, a, d_out);
   return hipGetLastError();
 }
 
-hipError_t launch_adam(const AdamArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s) {
+hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s) {
   const size_t lds = static_cast<size_t>(a.lds_entries) * sizeof(uint32_t);
-  if (nontemporal) hipLaunchKernelGGL(k_adam<true>, dim3(blocks), dim3(kThreads), lds, s, a);
-  else hipLaunchKernelGGL(k_adam<false>, dim3(blocks), dim3(kThreads), lds, s, a);
+  if (nt) hipLaunchKernelGGL(k_pack_persistent<true>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.segs, a.dst_off, a.ptrs, a);
+  else hipLaunchKernelGGL(k_pack_persistent<false>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.segs, a.dst_off, a.ptrs, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s) {
+  const size_t lds = static_cast<size_t>(a.lds_entries) * sizeof(uint32_t);
+  const uint64_t* header = reinterpret_cast<const uint64_t*>(a.packed);
+  if (nt) hipLaunchKernelGGL(k_unpack_persistent<true>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.segs, a.dst_off, a.ptrs, header, a);
+  else hipLaunchKernelGGL(k_unpack_persistent<false>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.segs, a.dst_off, a.ptrs, header, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_adam_persistent(const AdamArgs& a, uint32_t blocks, bool nt, hipStream_t s) {
+  const size_t lds = static_cast<size_t>(a.lds_entries) * sizeof(uint32_t);
+  if (nt) hipLaunchKernelGGL(k_adam_persistent<true>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.numel, a.op_of_tensor, a.mask, a.ptrs, a.grads, a);
+  else hipLaunchKernelGGL(k_adam_persistent<false>, dim3(blocks), dim3(kThreads), lds, s, a.tile_start, a.numel, a.op_of_tensor, a.mask, a.ptrs, a.grads, a);
   return hipGetLastError();
 }
 

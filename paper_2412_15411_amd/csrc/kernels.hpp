@@ -46,7 +46,7 @@ struct CopyArgs {
 };
 
 struct AdamArgs {
-  const uint32_t* tile_start;  // [n_tensors + 1]
+  const uint32_t* tile_start;  // [n_tensors + 1]: all tensors (fixed grid) or the step's active ones
   const uint64_t* numel;
   const uint32_t* op_of_tensor;
   const uint8_t* mask;
@@ -58,9 +58,23 @@ struct AdamArgs {
 };
 
 hipError_t launch_layout_scan(const ScanJob* d_jobs, uint32_t n_jobs, hipStream_t s);
-hipError_t launch_pack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
-hipError_t launch_unpack(const CopyArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
-hipError_t launch_adam(const AdamArgs& a, uint32_t blocks, bool nontemporal, hipStream_t s);
+hipError_t launch_copy_probe(const void* src, void* dst, uint64_t nbytes, uint32_t blocks, uint32_t unroll,
+                             bool nontemporal, hipStream_t s);
+
+// one tile per workgroup: grid = number of tiles, tile = threads * 16 bytes (* 4 elements) * unroll
+bool direct_shape_supported(uint32_t threads, uint32_t unroll);
+hipError_t launch_pack_direct(const CopyArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                              hipStream_t s);
+hipError_t launch_unpack_direct(const CopyArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                                hipStream_t s);
+hipError_t launch_active_scan(const AdamArgs& a, uint32_t* d_out, hipStream_t s);
+hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                              hipStream_t s);
+
+// fixed grid of 256-thread workgroups walking the tile list
+hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);
+hipError_t launch_unpack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);
+hipError_t launch_adam_persistent(const AdamArgs& a, uint32_t blocks, bool nt, hipStream_t s);
 
 constexpr uint32_t kThreads = 256;           // 4 wavefronts of 64
 constexpr uint32_t kMaxLdsEntries = 8192;    // 32 KB of tile_start in LDS at most; larger tables are searched in global memory

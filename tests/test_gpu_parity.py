@@ -76,17 +76,25 @@ class DeviceState:
             v.view(torch.int16).fill_(-1)
 
 
-def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=None, nt=None):
+def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=None, nt=None,
+              copy_shape=None, adam_shape=None):
+    """tile / blocks / adam_tile / adam_blocks select the fixed-grid launch shape with those values;
+    copy_shape / adam_shape = (threads, unroll) select a one-tile-per-workgroup shape (the default)."""
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
                        align=align)
-    if tile:
-        B.moev_tune(plan, B.TUNE_COPY_TILE_BYTES, tile)
-    if blocks:
-        B.moev_tune(plan, B.TUNE_COPY_MAX_BLOCKS, blocks)
-    if adam_tile:
-        B.moev_tune(plan, B.TUNE_ADAM_TILE_ELEMS, adam_tile)
-    if adam_blocks:
-        B.moev_tune(plan, B.TUNE_ADAM_MAX_BLOCKS, adam_blocks)
+    if tile or blocks or adam_tile or adam_blocks:
+        B.moev_tune(plan, B.TUNE_PERSISTENT, 1)
+    for knob, value in ((B.TUNE_COPY_TILE_BYTES, tile), (B.TUNE_COPY_MAX_BLOCKS, blocks),
+                        (B.TUNE_ADAM_TILE_ELEMS, adam_tile), (B.TUNE_ADAM_MAX_BLOCKS, adam_blocks)):
+        if value:
+            B.moev_tune(plan, knob, value)
+    for shape, k_threads, k_unroll in ((copy_shape, B.TUNE_COPY_THREADS, B.TUNE_COPY_UNROLL),
+                                       (copy_shape, B.TUNE_UNPACK_THREADS, B.TUNE_UNPACK_UNROLL),
+                                       (adam_shape, B.TUNE_ADAM_THREADS, B.TUNE_ADAM_UNROLL)):
+        if shape:
+            B.moev_tune(plan, k_unroll, 1)
+            B.moev_tune(plan, k_threads, shape[0])
+            B.moev_tune(plan, k_unroll, shape[1])
     if nt is not None:
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, nt)
     return plan
@@ -127,11 +135,13 @@ def _many_segments():
 @pytest.mark.parametrize("wl,align,tile", [
     (ragged_workload(1), 16, 4096), (ragged_workload(2), 256, 32768), (ragged_workload(3), 4096, 8192),
     (W.fine_grained_stack(n_layers=2, n_routed=64, n_shared=2, d_model=16, d_ff=11), 256, 4096),
-    (_many_segments(), 64, 4096),
-], ids=["ragged16", "ragged256", "ragged4096", "c2_small_888seg", "18000seg"])
+    (_many_segments(), 64, 4096), (ragged_workload(4), 256, None),
+], ids=["ragged16", "ragged256", "ragged4096", "c2_small_888seg", "18000seg", "default_shape"])
 def test_device_layout_scan_matches_oracle(orc, dev, wl, align, tile):
     """The wavefront prefix sums on the device reproduce the oracle's serial layout exactly."""
     plan = make_plan(wl, align=align, tile=tile)
+    if tile is None:
+        tile = B.moev_tune_get(plan, B.TUNE_COPY_THREADS) * 16 * B.moev_tune_get(plan, B.TUNE_COPY_UNROLL)
     model = model_of(wl, align=align)
     for k in range(wl.window):
         segs, total = orc.layout(model, k)
@@ -148,17 +158,19 @@ def test_device_layout_scan_matches_oracle(orc, dev, wl, align, tile):
 # ---------------------------------------------------------------------------------------
 # pack / drain / unpack
 # ---------------------------------------------------------------------------------------
-@pytest.mark.parametrize("seed,align,tile,blocks,nt", [
-    (1, 256, 32768, None, 1), (2, 16, 4096, 3, 1), (3, 4096, 8192, 7, 0), (4, 64, 65536, 1, 1), (5, 256, 32768, None, 0),
+@pytest.mark.parametrize("seed,align,tile,blocks,nt,shape", [
+    (1, 256, None, None, 1, None), (2, 16, None, None, 0, (64, 1)), (3, 4096, None, None, 1, (512, 2)),
+    (4, 64, None, None, 1, (256, 4)), (5, 256, None, None, 0, (1024, 1)), (6, 16, None, None, 1, (128, 1)),
+    (1, 256, 32768, None, 1, None), (2, 16, 4096, 3, 1, None), (3, 4096, 8192, 7, 0, None), (4, 64, 65536, 1, 1, None),
 ])
-def test_pack_bit_exact(orc, dev, seed, align, tile, blocks, nt):
+def test_pack_bit_exact(orc, dev, seed, align, tile, blocks, nt, shape):
     """Ragged tensors with arbitrary bit patterns: GPU packed buffer == oracle packed buffer, byte
     for byte (header, segments, zero padding), for every slot; the source state is not modified."""
     wl = ragged_workload(seed)
     st_cpu = W.random_bits_state(wl, seed=seed)
     ds = DeviceState(st_cpu, dev)
     ref_state = state_of(st_cpu)
-    plan, model = make_plan(wl, align=align, tile=tile, blocks=blocks, nt=nt), model_of(wl, align=align)
+    plan, model = make_plan(wl, align=align, tile=tile, blocks=blocks, nt=nt, copy_shape=shape), model_of(wl, align=align)
     buf = packed_buffer(plan, dev)
     for k in range(wl.window):
         buf.fill_(0xA5)
@@ -171,15 +183,17 @@ def test_pack_bit_exact(orc, dev, seed, align, tile, blocks, nt):
     assert states_equal(ds.to_oracle(), ref_state) == [] and ds.guards_intact()
 
 
-@pytest.mark.parametrize("seed,align,tile,blocks", [(11, 256, 32768, None), (12, 16, 4096, 5), (13, 4096, 16384, 2)])
-def test_unpack_bit_exact_with_sentinels(orc, dev, seed, align, tile, blocks):
+@pytest.mark.parametrize("seed,align,tile,blocks,shape", [
+    (11, 256, None, None, None), (12, 16, None, None, (64, 1)), (13, 4096, None, None, (512, 2)), (14, 64, None, None, (256, 4)),
+    (15, 256, None, None, (1024, 1)), (11, 256, 32768, None, None), (12, 16, 4096, 5, None), (13, 4096, 16384, 2, None)])
+def test_unpack_bit_exact_with_sentinels(orc, dev, seed, align, tile, blocks, shape):
     """restore_unpack of an ORACLE-made snapshot into a poisoned device state equals the oracle's
     unpack: restored tensors, derived bf16 weights of the newly active operators, untouched
     tensors, guard gaps and the active mask."""
     wl = ragged_workload(seed)
     model = model_of(wl, align=align)
     truth = state_of(W.random_bits_state(wl, seed=seed))
-    plan = make_plan(wl, align=align, tile=tile, blocks=blocks)
+    plan = make_plan(wl, align=align, tile=tile, blocks=blocks, copy_shape=shape)
     st_cpu = W.random_bits_state(wl, seed=seed + 100)
     for k in range(wl.window):
         ds = DeviceState(st_cpu, dev)
@@ -321,10 +335,13 @@ def _compare_adam(ds, ref, label=""):
     return worst
 
 
-@pytest.mark.parametrize("seed,wd,heavy,adam_tile,blocks,nt", [
-    (1, 0.0, False, 8192, None, 1), (2, 0.1, True, 1024, 3, 1), (3, 0.0, True, 4096, 1, 0), (4, 0.01, False, 16384, 9, 0),
+@pytest.mark.parametrize("seed,wd,heavy,adam_tile,blocks,nt,shape", [
+    (1, 0.0, False, None, None, 1, None), (2, 0.1, True, None, None, 0, (64, 1)), (3, 0.0, True, None, None, 1, (512, 2)),
+    (4, 0.01, False, None, None, 1, (256, 4)), (5, 0.0, False, None, None, 0, (1024, 1)),
+    (1, 0.0, False, 8192, None, 1, None), (2, 0.1, True, 1024, 3, 1, None), (3, 0.0, True, 4096, 1, 0, None),
+    (4, 0.01, False, 16384, 9, 0, None),
 ])
-def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt):
+def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt, shape):
     """One replayed iteration on ragged tensors with a mixed active/frozen mask: FP32 state within
     1e-6 relative of the oracle (expected bit-identical), frozen tensors and guards untouched."""
     wl = ragged_workload(40 + seed)
@@ -333,7 +350,7 @@ def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks
     st_cpu = W.make_state(wl, seed=seed)
     ds = DeviceState(st_cpu, dev)
     ref = state_of(st_cpu)
-    plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt)
+    plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt, adam_shape=shape)
     rng = np.random.default_rng(seed)
     mask_np = (rng.random(wl.n_ops) < 0.6).astype(np.uint8)
     mask_np[0] = 1
@@ -341,6 +358,8 @@ def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks
     for step in (11, 12, 13):
         grads_cpu = W.make_grads(wl, step, seed=seed)
         grads_dev = [g.to(dev) for g in grads_cpu]
+        if step == 12:  # frozen operators have no weight gradients: their entries may be missing
+            grads_dev = [g if mask_np[wl.tensors[t][0]] else None for t, g in enumerate(grads_dev)]
         B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, step, mask, grads_dev, ds.state)
         torch.cuda.synchronize()
         orc.replay_step(model, hp, step, mask_np, [np_of(g) for g in grads_cpu], ref)
@@ -444,6 +463,13 @@ def test_window_conversion_stress_small(orc, dev):
     rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=4, via_host=True, tile=4096, adam_tile=1024)
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "c4-small")
+
+
+def test_window_ragged_direct_shapes(orc, dev):
+    wl = ragged_workload(78, n_ops=9, window=3, with_empty=True)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=6, align=64, copy_shape=(512, 2), adam_shape=(128, 1))
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "ragged-window-direct")
 
 
 def test_window_ragged_small_grid(orc, dev):

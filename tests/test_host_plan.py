@@ -142,7 +142,10 @@ def test_tune_knobs_validate():
     assert B.moev_tune_get(plan, B.TUNE_COPY_TILE_BYTES) % 4096 == 0
     B.moev_tune(plan, B.TUNE_COPY_TILE_BYTES, 65536)
     assert B.moev_tune_get(plan, B.TUNE_COPY_TILE_BYTES) == 65536
-    for knob, value in [(B.TUNE_COPY_TILE_BYTES, 1000), (B.TUNE_ADAM_TILE_ELEMS, 100), (B.TUNE_COPY_MAX_BLOCKS, -1), (99, 1)]:
+    B.moev_tune(plan, B.TUNE_COPY_THREADS, 512)
+    B.moev_tune(plan, B.TUNE_COPY_UNROLL, 2)
+    for knob, value in [(B.TUNE_COPY_TILE_BYTES, 1000), (B.TUNE_ADAM_TILE_ELEMS, 100), (B.TUNE_COPY_MAX_BLOCKS, -1), (99, 1),
+                        (B.TUNE_COPY_UNROLL, 4), (B.TUNE_COPY_THREADS, 100), (B.TUNE_ADAM_UNROLL, 3)]:
         with pytest.raises(B.MoevError):
             B.moev_tune(plan, knob, value)
 
