@@ -255,6 +255,26 @@ def main():
         "roofline": roofline,
     }
 
+    # ---- plain contiguous copy of known size: the box's practical copy ceiling, and the kernel
+    # against which the rocprofv3 HBM counters are calibrated ----------------------------------
+    probe_bytes = 4 << 30
+    src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        B.moev_copy_probe(dst, src, probe_bytes, 0, 1, stream)
+        e1.record(stream)
+        stream.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    out["copy_probe"] = {"bytes_each_way": probe_bytes, "ms": round(best, 4),
+                         "GBs": round(2 * probe_bytes / (best / 1e3) / 1e9, 1),
+                         "frac_hbm_peak": round(2 * probe_bytes / (best / 1e3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del src, dst
+
     # ---- drain: host link, measured outside the timed steps --------------------------------
     if not args.no_drain:
         k = 0
