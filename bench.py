@@ -36,10 +36,11 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="c1", choices=["c0", "c1", "c2", "c4"])
+    ap.add_argument("--config", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--no-drain", action="store_true", help="skip the host-link drain measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--overlap", action="store_true", help="also time the drain under a concurrent bf16 GEMM loop")
+    ap.add_argument("--drain-last-slot", action="store_true", help="configs[3]: overlap/drain measurements on the last slot (19 GB) instead of slot 0 (42 GB)")
     ap.add_argument("--persistent", action="store_true", help="fixed-grid launch shape (LDS-staged tile table)")
     ap.add_argument("--copy-tile", type=int, default=0)
     ap.add_argument("--adam-tile", type=int, default=0)
@@ -138,6 +139,176 @@ def cpu_baseline(cfg_name, seed):
 
 
 # ---------------------------------------------------------------------------------------
+def rank_share_bench(args, torch, B, W, dev):
+    """configs[3]: one GPU's share of a large MoE (180 GB of state resident in HBM).  The packed
+    snapshots of a window (245 GB) cannot be resident next to the state, so a step here is
+    W x (snapshot_pack into one reused buffer, restore_unpack from it); the replay is not part of
+    this configuration.  Also measured: the pack and the drain while a bf16 GEMM loop runs on the
+    main stream (the overlap the method relies on, Sec. 3.2 / Sec. 4)."""
+    wl = W.ep_rank_share()
+    t_setup = time.time()
+    log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
+    st = W.make_state(wl, seed=args.seed, device=dev)
+    state = B.State(st["master"], st["m"], st["v"], st["compute"])
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+    packed = torch.empty(B.ckpt_plan_max_packed_bytes(plan), dtype=torch.uint8, device=dev)
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    B.ckpt_plan_upload(plan, main)
+    torch.cuda.synchronize()
+    log(f"[bench] inputs resident in HBM after {time.time() - t_setup:.1f} s; {torch.cuda.memory_allocated() / 1e9:.1f} GB allocated")
+
+    timings = []
+
+    def timed(kind, nbytes, fn, record, stream):
+        if record:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            timings.append((kind, nbytes, e0, e1))
+        else:
+            fn()
+
+    def one_step(record):
+        for k in range(wl.window):
+            timed("pack", pack_bytes(wl, k), lambda: B.snapshot_pack(plan, k, wl.t0 + k, state, packed, stream=main), record, main)
+            timed("unpack", unpack_bytes(wl, k), lambda: B.restore_unpack(plan, k, None, packed, state, mask, stream=main), record, main)
+
+    step_bytes = sum(pack_bytes(wl, k) + unpack_bytes(wl, k) for k in range(wl.window))
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.ckpt_plan_device_status(plan, main)
+    per_kind = {}
+    for kind, nbytes, e0, e1 in timings:
+        d = per_kind.setdefault(kind, {"bytes": 0, "ms": 0.0, "launches": 0})
+        d["bytes"] += nbytes
+        d["ms"] += e0.elapsed_time(e1)
+        d["launches"] += 1
+    kernels = {}
+    for kind, d in per_kind.items():
+        gbs = d["bytes"] / (d["ms"] / 1e3) / 1e9
+        kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
+                         "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
+    value = step_bytes / (elapsed / args.steps) / 1e9
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"configs[3] {wl.name}", "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
+                   "step": "W x (snapshot_pack + restore_unpack) through one reused packed buffer, HBM-resident; no replay",
+                   "step_algorithmic_bytes": step_bytes},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4), "kernels": kernels,
+        "roofline": {"bound": "hbm", "kernel": "k_unpack_direct", "achieved": kernels["unpack"]["GBs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": kernels["unpack"]["frac_hbm_peak"], "traffic": read_traffic("k_unpack_direct", "c3")},
+    }
+
+    # ---- overlap: pack and drain of slot `k` against a bf16 GEMM loop on the main stream -------
+    k = wl.window - 1 if args.drain_last_slot else 0
+    nbytes = B.ckpt_plan_packed_bytes(plan, k)
+    a = torch.randn(8192, 4096, dtype=torch.bfloat16, device=dev)
+    b = torch.randn(4096, 2048, dtype=torch.bfloat16, device=dev)
+    c = torch.empty(8192, 2048, dtype=torch.bfloat16, device=dev)
+
+    def gemm_loop(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(main):
+            e0.record(main)
+            for _ in range(n):
+                torch.mm(a, b, out=c)
+            e1.record(main)
+        return e0, e1
+
+    gemm_loop(50)                      # warm-up: library initialisation and kernel selection
+    torch.cuda.synchronize()
+    g0, g1 = gemm_loop(200)
+    torch.cuda.synchronize()
+    per_gemm_ms = g0.elapsed_time(g1) / 200
+    gemm_tflops = 2 * 8192 * 4096 * 2048 / (per_gemm_ms / 1e3) / 1e12
+
+    def pack_on_side(p):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        B.snapshot_pack(p, k, wl.t0 + k, state, packed, stream=side)
+        e1.record(side)
+        return e0, e1
+
+    # the default shape floods the dispatcher with small workgroups; the fixed-grid shape with a cap
+    # on its workgroups leaves compute units to the GEMM
+    overlap = []
+    for label, cap in (("one tile per workgroup (default)", None), ("fixed grid, 2048 workgroups", 2048),
+                       ("fixed grid, 1024 workgroups", 1024), ("fixed grid, 512 workgroups", 512),
+                       ("fixed grid, 256 workgroups", 256)):
+        p = plan
+        if cap is not None:
+            p = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+            B.moev_tune(p, B.TUNE_PERSISTENT, 1)
+            B.moev_tune(p, B.TUNE_COPY_MAX_BLOCKS, cap)
+        p0, p1 = pack_on_side(p)
+        torch.cuda.synchronize()
+        p0, p1 = pack_on_side(p)
+        torch.cuda.synchronize()
+        pack_alone_ms = p0.elapsed_time(p1)
+        n_gemm = max(50, int(3 * pack_alone_ms / per_gemm_ms))
+        g0, g1 = gemm_loop(n_gemm)
+        torch.cuda.synchronize()
+        gemm_alone_ms = g0.elapsed_time(g1)
+        g0, g1 = gemm_loop(n_gemm)
+        p0, p1 = pack_on_side(p)
+        torch.cuda.synchronize()
+        overlap.append({
+            "pack_shape": label, "n_gemm": n_gemm,
+            "pack_ms_alone": round(pack_alone_ms, 3), "pack_ms_with_gemm": round(p0.elapsed_time(p1), 3),
+            "pack_GBs_alone": round(pack_bytes(wl, k) / (pack_alone_ms / 1e3) / 1e9, 1),
+            "pack_GBs_with_gemm": round(pack_bytes(wl, k) / (p0.elapsed_time(p1) / 1e3) / 1e9, 1),
+            "gemm_ms_alone": round(gemm_alone_ms, 3), "gemm_ms_with_pack": round(g0.elapsed_time(g1), 3),
+            "gemm_ms_lost": round(g0.elapsed_time(g1) - gemm_alone_ms, 3)})
+        del p
+    out["pack_under_gemm"] = {"slot": k, "gemm": "bf16 [8192x4096]x[4096x2048] back to back on the main stream",
+                              "gemm_TFLOPs_alone": round(gemm_tflops, 1), "runs": overlap}
+
+    if not args.no_drain:
+        t_pin = time.time()
+        host = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+        log(f"[bench] pinned {nbytes / 1e9:.1f} GB of host memory in {time.time() - t_pin:.1f} s")
+        done = torch.cuda.Event()
+        B.snapshot_pack(plan, k, wl.t0 + k, state, packed, stream=main)
+        done.record(main)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        B.snapshot_drain(plan, k, packed, host, side_stream=side, pack_done=done)
+        e1.record(side)
+        torch.cuda.synchronize()
+        drain_alone_ms = e0.elapsed_time(e1)
+        n_gemm = max(20, int(1.2 * drain_alone_ms / per_gemm_ms))
+        g0, g1 = gemm_loop(n_gemm)
+        torch.cuda.synchronize()
+        gemm_alone_ms = g0.elapsed_time(g1)
+        g0, g1 = gemm_loop(n_gemm)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        B.snapshot_drain(plan, k, packed, host, side_stream=side)
+        e1.record(side)
+        torch.cuda.synchronize()
+        out["drain"] = {"bound": "host-link", "slot": k, "bytes": nbytes, "ms": round(drain_alone_ms, 2),
+                        "GBs": round(nbytes / (drain_alone_ms / 1e3) / 1e9, 2),
+                        "header_ok": B.snapshot_peek(plan, k, host)["slot"] == k}
+        out["drain_under_gemm"] = {
+            "gemm": "bf16 [8192x4096]x[4096x2048], %d back to back on the main stream" % n_gemm,
+            "drain_ms": round(e0.elapsed_time(e1), 2), "drain_GBs": round(nbytes / (e0.elapsed_time(e1) / 1e3) / 1e9, 2),
+            "gemm_ms_alone": round(gemm_alone_ms, 2), "gemm_ms_with_drain": round(g0.elapsed_time(g1), 2)}
+        del host
+    print(json.dumps(out), flush=True)
+
+
+# ---------------------------------------------------------------------------------------
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -155,6 +326,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.config == "c3":
+        return rank_share_bench(args, torch, B, W, dev)
     wl = W.CONFIGS[args.config]()
     t_setup = time.time()
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
