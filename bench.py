@@ -428,6 +428,35 @@ def main():
         "roofline": roofline,
     }
 
+    # ---- the same conversion with the fused load-and-replay call (convert_window_step) ----------
+    def fused_window():
+        mask.zero_()
+        for i in range(wl.window):
+            B.convert_window_step(plan, i, None, packed[i], wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay,
+                                  wl.t0 + i + 1, mask, grads[wl.t0 + i + 1], state, stream=stream)
+
+    fused_bytes = 0
+    for i in range(wl.window):
+        frozen = sum(p for e, p in enumerate(wl.params_of_op()) if wl.slot_of_op[e] > i)
+        fused_bytes += 2 * 2 * frozen + replay_bytes(wl, i)   # compute-weight copies + 30 B per active parameter
+    with torch.cuda.stream(stream):
+        fused_window()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            fused_window()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan, stream)
+    fused_ms = e0.elapsed_time(e1) / args.steps
+    two_call_ms = (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / args.steps
+    out["fused_conversion"] = {
+        "call": "convert_window_step (restore_unpack + convert_replay in one pass, same results)",
+        "ms_per_window": round(fused_ms, 3), "two_call_ms_per_window": round(two_call_ms, 3),
+        "iters_per_s": round(wl.window / (fused_ms / 1e3), 2),
+        "algorithmic_bytes": fused_bytes, "GBs": round(fused_bytes / (fused_ms / 1e3) / 1e9, 1)}
+
     # ---- plain contiguous copy of known size: the box's practical copy ceiling, and the kernel
     # against which the rocprofv3 HBM counters are calibrated ----------------------------------
     probe_bytes = 4 << 30

@@ -252,6 +252,18 @@ int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d
 int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
                    void *const *grads, const moev_state *state, void *stream);
 
+/* convert_window_step: one step of the conversion loop (Sec. 3.3: load SS_t, then replay iteration
+ * t+1), i.e. restore_unpack(slot) followed by convert_replay(adam) with bit-identical results, but
+ * fused: the FP32 state of the operators the snapshot activates is read straight from the packed
+ * buffer by the replay kernel instead of being scattered to the dense tensors and read back
+ * (26 fewer bytes of HBM traffic per newly active parameter).  Arguments as in the two calls;
+ * d_active_mask is updated like restore_unpack does and then used like convert_replay does.
+ * Every tensor of an operator active in `slot` must have a gradient (MOEV_E_INVAL otherwise).
+ * A foreign device-resident snapshot is refused as a whole (status word, nothing is modified). */
+int convert_window_step(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d_packed,
+                        const moev_adam *adam, uint8_t *d_active_mask, void *const *grads,
+                        const moev_state *state, void *stream);
+
 /* ---- measurement hook --------------------------------------------------------------------
  * moev_copy_probe: plain contiguous device-to-device copy of nbytes (multiple of 16, both
  * pointers 16-byte aligned) with the same access shape as the gather kernel.  It is the

@@ -28,7 +28,8 @@ EXPORTS = [
     "ckpt_plan_hash", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
-    "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "moev_copy_probe",
+    "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
+    "moev_copy_probe",
 ]
 
 
@@ -112,6 +113,7 @@ def _load():
     lib.snapshot_peek.argtypes = [vp, u32, vp, C.POINTER(_Header)]
     lib.restore_unpack.argtypes = [vp, u32, vp, vp, C.POINTER(_State), vp, vp]
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
+    lib.convert_window_step.argtypes = [vp, u32, vp, vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
     return lib
 
@@ -195,7 +197,7 @@ class Plan:
 
     def __del__(self):
         h, self.handle = getattr(self, "handle", None), None
-        if h:
+        if h and _lib is not None:  # at interpreter shutdown the module globals may already be gone
             _lib.ckpt_plan_free(h)
 
 
@@ -311,6 +313,14 @@ def convert_replay(plan, lr, beta1, beta2, eps, weight_decay, step: int, d_activ
     g = _ptr_array(grads)
     _check(_lib.convert_replay(plan.handle, C.byref(adam), _addr(d_active_mask), g, C.byref(state.c),
                                _stream(stream)))
+
+
+def convert_window_step(plan, slot: int, h_pinned, d_packed, lr, beta1, beta2, eps, weight_decay, step: int,
+                        d_active_mask, grads: Sequence, state: State, stream=None):
+    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step)
+    g = _ptr_array(grads)
+    _check(_lib.convert_window_step(plan.handle, slot, _addr(h_pinned), _addr(d_packed), C.byref(adam),
+                                    _addr(d_active_mask), g, C.byref(state.c), _stream(stream)))
 
 
 def moev_copy_probe(d_dst, d_src, nbytes: int, blocks: int = 0, nontemporal: int = 1, stream=None):

@@ -3,6 +3,7 @@
 // method happens on the host: every byte moved and every Adam update runs in the kernels.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -93,6 +94,8 @@ struct moev_plan {
   StageSlot ring[kRing];
   int ring_next = 0;
   std::vector<uint32_t> slot_tiles, slot_tiles_unpack;  // host-side tile counts (grid sizing only)
+  std::vector<uint32_t> slot_first_compute_tile;        // unpack tiles in front of the first compute segment
+  uint64_t* d_src_off = nullptr;            // [window][3][n_tensors] snapshot offsets of master, m, v (~0: absent)
   uint32_t tensor_tiles = 0;
 
   ~moev_plan() {
@@ -127,15 +130,19 @@ void compute_host_tiles(moev_plan* pl) {
   const auto& h = pl->host;
   pl->slot_tiles.assign(h.window, 0);
   pl->slot_tiles_unpack.assign(h.window, 0);
+  pl->slot_first_compute_tile.assign(h.window, 0);
   for (uint32_t k = 0; k < h.window; ++k) {
-    uint64_t n = 0, nu = 0;
+    uint64_t n = 0, nu = 0, nu_fp32 = 0;
     for (uint32_t j = 0; j < h.slots[k].n_segments; ++j) {
-      const uint64_t padded = round_up(h.segments[h.slots[k].first_segment + j].nbytes, h.align);
+      const moev_segment& sg = h.segments[h.slots[k].first_segment + j];
+      const uint64_t padded = round_up(sg.nbytes, h.align);
       n += tiles_of(padded, pl->eff_copy_tile());
       nu += tiles_of(padded, pl->eff_unpack_tile());
+      if (sg.kind != MOEV_KIND_COMPUTE) nu_fp32 = nu;  // full-state segments come first in a slot
     }
     pl->slot_tiles[k] = static_cast<uint32_t>(n);
     pl->slot_tiles_unpack[k] = static_cast<uint32_t>(nu);
+    pl->slot_first_compute_tile[k] = static_cast<uint32_t>(nu_fp32);
   }
   uint64_t n = 0;
   for (const auto& t : h.tensors) n += tiles_of(t.numel, pl->eff_adam_tile());
@@ -160,6 +167,7 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
   const size_t o_numel = carve(h.n_tensors * sizeof(uint64_t));
   const size_t o_opt = carve(h.n_tensors * sizeof(uint32_t));
   const size_t o_slot = carve(h.n_ops * sizeof(uint32_t));
+  const size_t o_src = carve(3ull * h.window * h.n_tensors * sizeof(uint64_t));
   const size_t o_jobs = carve((2 * h.window + 1) * sizeof(moev::ScanJob));
   const size_t input_bytes = off;
   const size_t o_dst = carve(n_seg * sizeof(uint64_t));
@@ -184,6 +192,7 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
   pl->d_op_of_tensor = reinterpret_cast<uint32_t*>(d + o_opt);
   pl->d_slot_of_op = reinterpret_cast<uint32_t*>(d + o_slot);
   pl->d_jobs = reinterpret_cast<moev::ScanJob*>(d + o_jobs);
+  pl->d_src_off = reinterpret_cast<uint64_t*>(d + o_src);
   pl->d_dst_off = reinterpret_cast<uint64_t*>(d + o_dst);
   pl->d_seg_tile_start = reinterpret_cast<uint32_t*>(d + o_tile);
   pl->d_seg_tile_start_unpack = reinterpret_cast<uint32_t*>(d + o_utile);
@@ -203,6 +212,14 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
     opt[t] = h.tensors[t].op;
   }
   std::memcpy(m + o_slot, h.slot_of_op.data(), h.n_ops * sizeof(uint32_t));
+  auto* src_off = reinterpret_cast<uint64_t*>(m + o_src);
+  std::fill(src_off, src_off + 3ull * h.window * h.n_tensors, ~0ull);
+  for (uint32_t k = 0; k < h.window; ++k)
+    for (uint32_t j = 0; j < h.slots[k].n_segments; ++j) {
+      const moev_segment& sg = h.segments[h.slots[k].first_segment + j];
+      if (sg.kind != MOEV_KIND_COMPUTE)
+        src_off[(3ull * k + sg.kind) * h.n_tensors + sg.tensor] = sg.dst_off;
+    }
   MOEV_HIP(hipMemsetAsync(pl->d_status, 0, sizeof(uint32_t), s));
   return MOEV_OK;
 }
@@ -348,6 +365,128 @@ int check_slot_pointers(const moev_plan* pl, uint32_t slot, const moev_state* st
       if (!c || !aligned16(c))
         return fail(MOEV_E_INVAL, "%s: compute pointer of tensor %u is null or not 16-byte aligned", who, sg.tensor);
     }
+  }
+  return MOEV_OK;
+}
+
+int check_unpack_args(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_state* state,
+                      const char* who) {
+  if (!p || !d_packed) return fail(MOEV_E_INVAL, "%s: null argument", who);
+  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "%s: slot %u outside window %u", who, slot, p->host.window);
+  if (reinterpret_cast<uintptr_t>(d_packed) & 255u) return fail(MOEV_E_INVAL, "%s: d_packed must be 256-byte aligned", who);
+  int rc = check_state(p, state, who);
+  if (rc != MOEV_OK) return rc;
+  const auto& h = p->host;
+  const bool derive = h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2;
+  rc = check_slot_pointers(p, slot, state, derive, who);
+  if (rc != MOEV_OK) return rc;
+  if (h_pinned) {
+    rc = snapshot_peek(p, slot, h_pinned, nullptr);
+    if (rc != MOEV_OK) return rc;
+  }
+  return MOEV_OK;
+}
+
+// (optional H2D copy and) the scatter kernel.  compute_only: scatter just the compute-weight segments
+// (the tail of the slot's segment list); the FP32 segments are consumed in place by the fused replay.
+int launch_unpack_locked(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_state* state,
+                         uint8_t* d_active_mask, hipStream_t s, bool compute_only) {
+  const auto& h = p->host;
+  int rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  if (h_pinned)
+    MOEV_HIP(hipMemcpyAsync(d_packed, h_pinned, h.slots[slot].packed_bytes, hipMemcpyHostToDevice, s));
+  moev::CopyArgs a = copy_args(p, slot, 0, d_packed, true);
+  a.mask = d_active_mask;
+  a.derive_compute = (h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2) ? 1u : 0u;
+  if (p->persistent) {
+    MOEV_HIP(moev::launch_unpack_persistent(a, grid_for(p, p->slot_tiles_unpack[slot], p->copy_max_blocks), p->nontemporal != 0, s));
+  } else {
+    a.tile_begin = compute_only ? p->slot_first_compute_tile[slot] : 0u;
+    const uint32_t tiles = p->slot_tiles_unpack[slot] - a.tile_begin;
+    MOEV_HIP(moev::launch_unpack_direct(a, tiles ? tiles : 1u, static_cast<uint32_t>(p->unpack_threads),
+                                        static_cast<uint32_t>(p->unpack_unroll), p->nontemporal != 0, s));
+  }
+  return MOEV_OK;
+}
+
+int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
+                      const moev_state* state, const char* who) {
+  if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "%s: null argument", who);
+  const auto& h = p->host;
+  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_COMPUTE] != 2)
+    return fail(MOEV_E_INVAL, "%s: needs FP32 master and moments and 2-byte compute weights", who);
+  if (adam->step == 0) return fail(MOEV_E_INVAL, "%s: step counts from 1", who);
+  int rc = check_state(p, state, who);
+  if (rc != MOEV_OK) return rc;
+  void* const* table[4] = {state->master, state->m, state->v, state->compute};
+  for (uint32_t t = 0; t < h.n_tensors; ++t) {
+    if (h.tensors[t].numel == 0) continue;  // an empty tensor is never dereferenced
+    for (int k = 0; k < 4; ++k)
+      if (!table[k][t] || !aligned16(table[k][t]))
+        return fail(MOEV_E_INVAL, "%s: tensor %u kind %d pointer is null or not 16-byte aligned", who, t, k);
+    if (!aligned16(grads[t])) return fail(MOEV_E_INVAL, "%s: gradient %u is not 16-byte aligned", who, t);
+  }
+  return MOEV_OK;
+}
+
+// fused_slot >= 0: the FP32 state of the tensors that slot activates is read from d_packed
+int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
+                         const moev_state* state, hipStream_t s, int fused_slot, const void* d_packed) {
+  const auto& h = p->host;
+  int rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  std::vector<void*> g(grads, grads + h.n_tensors);
+  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s);
+  if (rc != MOEV_OK) return rc;
+
+  moev::AdamArgs a{};
+  a.tile_start = p->d_tensor_tile_start;
+  a.numel = p->d_numel;
+  a.op_of_tensor = p->d_op_of_tensor;
+  a.mask = d_active_mask;
+  a.ptrs = p->d_state_ptrs;
+  a.grads = p->d_grad_ptrs;
+  a.status = p->d_status;
+  a.n_tensors = h.n_tensors;
+  a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
+  a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
+  a.lr = adam->lr;
+  a.beta1 = adam->beta1;
+  a.beta2 = adam->beta2;
+  a.eps = adam->eps;
+  a.one_minus_beta1 = 1.0f - adam->beta1;
+  a.one_minus_beta2 = 1.0f - adam->beta2;
+  // bias corrections 1 - beta^step: in double, rounded to FP32 once
+  a.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta1), static_cast<double>(adam->step)));
+  a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
+  a.decay = adam->lr * adam->weight_decay;
+  a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
+  if (p->persistent) {
+    MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
+    return MOEV_OK;
+  }
+  // The device compacts the tile list to the tensors that are active (mask) and have gradients;
+  // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles.
+  uint64_t bound = 0;
+  for (uint32_t t = 0; t < h.n_tensors; ++t)
+    if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
+  if (bound == 0) bound = 1;
+  MOEV_HIP(moev::launch_active_scan(a, p->d_active_tile_start, s));
+  a.tile_start = p->d_active_tile_start;
+  if (fused_slot >= 0) {
+    a.src_off = p->d_src_off + 3ull * h.n_tensors * static_cast<uint32_t>(fused_slot);
+    a.packed = static_cast<const uint8_t*>(d_packed);
+    fill_header(p, static_cast<uint32_t>(fused_slot), 0, a.header);
+    MOEV_HIP(moev::launch_adam_fused(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
+                                     static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
+  } else {
+    MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
+                                      static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
   }
   return MOEV_OK;
 }
@@ -678,103 +817,37 @@ int snapshot_peek(const moev_plan* p, uint32_t slot, const void* h_packed, moev_
 
 int restore_unpack(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_state* state,
                    uint8_t* d_active_mask, void* stream) {
-  if (!p || !d_packed) return fail(MOEV_E_INVAL, "restore_unpack: null argument");
-  if (slot >= p->host.window) return fail(MOEV_E_RANGE, "restore_unpack: slot %u outside window %u", slot, p->host.window);
-  if (reinterpret_cast<uintptr_t>(d_packed) & 255u) return fail(MOEV_E_INVAL, "restore_unpack: d_packed must be 256-byte aligned");
-  int rc = check_state(p, state, "restore_unpack");
+  int rc = check_unpack_args(p, slot, h_pinned, d_packed, state, "restore_unpack");
   if (rc != MOEV_OK) return rc;
-  const auto& h = p->host;
-  const bool derive = h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2;
-  rc = check_slot_pointers(p, slot, state, derive, "restore_unpack");
-  if (rc != MOEV_OK) return rc;
-  if (h_pinned) {
-    rc = snapshot_peek(p, slot, h_pinned, nullptr);
-    if (rc != MOEV_OK) return rc;
-  }
   std::lock_guard<std::mutex> lock(p->mu);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = upload_locked(p, s);
-  if (rc != MOEV_OK) return rc;
-  rc = bind_state(p, state, s);
-  if (rc != MOEV_OK) return rc;
-  if (h_pinned)
-    MOEV_HIP(hipMemcpyAsync(d_packed, h_pinned, h.slots[slot].packed_bytes, hipMemcpyHostToDevice, s));
-  moev::CopyArgs a = copy_args(p, slot, 0, d_packed, true);
-  a.mask = d_active_mask;
-  a.derive_compute = derive ? 1u : 0u;
-  if (p->persistent)
-    MOEV_HIP(moev::launch_unpack_persistent(a, grid_for(p, p->slot_tiles_unpack[slot], p->copy_max_blocks), p->nontemporal != 0, s));
-  else
-    MOEV_HIP(moev::launch_unpack_direct(a, p->slot_tiles_unpack[slot] ? p->slot_tiles_unpack[slot] : 1u,
-                                        static_cast<uint32_t>(p->unpack_threads), static_cast<uint32_t>(p->unpack_unroll),
-                                        p->nontemporal != 0, s));
-  return MOEV_OK;
+  return launch_unpack_locked(p, slot, h_pinned, d_packed, state, d_active_mask, static_cast<hipStream_t>(stream), false);
 }
 
 int convert_replay(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
                    const moev_state* state, void* stream) {
-  if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "convert_replay: null argument");
-  const auto& h = p->host;
-  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_COMPUTE] != 2)
-    return fail(MOEV_E_INVAL, "convert_replay: needs FP32 master and moments and 2-byte compute weights");
-  if (adam->step == 0) return fail(MOEV_E_INVAL, "convert_replay: step counts from 1");
-  int rc = check_state(p, state, "convert_replay");
+  int rc = check_replay_args(p, adam, d_active_mask, grads, state, "convert_replay");
   if (rc != MOEV_OK) return rc;
-  void* const* table[4] = {state->master, state->m, state->v, state->compute};
-  for (uint32_t t = 0; t < h.n_tensors; ++t) {
-    if (h.tensors[t].numel == 0) continue;  // an empty tensor is never dereferenced
-    for (int k = 0; k < 4; ++k)
-      if (!table[k][t] || !aligned16(table[k][t]))
-        return fail(MOEV_E_INVAL, "convert_replay: tensor %u kind %d pointer is null or not 16-byte aligned", t, k);
-    if (!aligned16(grads[t])) return fail(MOEV_E_INVAL, "convert_replay: gradient %u is not 16-byte aligned", t);
-  }
+  std::lock_guard<std::mutex> lock(p->mu);
+  return launch_replay_locked(p, adam, d_active_mask, grads, state, static_cast<hipStream_t>(stream), -1, nullptr);
+}
+
+int convert_window_step(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_adam* adam,
+                        uint8_t* d_active_mask, void* const* grads, const moev_state* state, void* stream) {
+  int rc = check_unpack_args(p, slot, h_pinned, d_packed, state, "convert_window_step");
+  if (rc != MOEV_OK) return rc;
+  rc = check_replay_args(p, adam, d_active_mask, grads, state, "convert_window_step");
+  if (rc != MOEV_OK) return rc;
+  const auto& h = p->host;
+  // the operators this snapshot activates take their first replayed step right away: they need gradients
+  for (uint32_t t = 0; t < h.n_tensors; ++t)
+    if (h.slot_of_op[h.tensors[t].op] == slot && h.tensors[t].numel && !grads[t])
+      return fail(MOEV_E_INVAL, "convert_window_step: tensor %u becomes active in slot %u but has no gradient", t, slot);
   std::lock_guard<std::mutex> lock(p->mu);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = upload_locked(p, s);
+  const bool fused = !p->persistent;
+  rc = launch_unpack_locked(p, slot, h_pinned, d_packed, state, d_active_mask, s, fused);
   if (rc != MOEV_OK) return rc;
-  rc = bind_state(p, state, s);
-  if (rc != MOEV_OK) return rc;
-  std::vector<void*> g(grads, grads + h.n_tensors);
-  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s);
-  if (rc != MOEV_OK) return rc;
-
-  moev::AdamArgs a{};
-  a.tile_start = p->d_tensor_tile_start;
-  a.numel = p->d_numel;
-  a.op_of_tensor = p->d_op_of_tensor;
-  a.mask = d_active_mask;
-  a.ptrs = p->d_state_ptrs;
-  a.grads = p->d_grad_ptrs;
-  a.status = p->d_status;
-  a.n_tensors = h.n_tensors;
-  a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
-  a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
-  a.lr = adam->lr;
-  a.beta1 = adam->beta1;
-  a.beta2 = adam->beta2;
-  a.eps = adam->eps;
-  a.one_minus_beta1 = 1.0f - adam->beta1;
-  a.one_minus_beta2 = 1.0f - adam->beta2;
-  // bias corrections 1 - beta^step: in double, rounded to FP32 once
-  a.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta1), static_cast<double>(adam->step)));
-  a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
-  a.decay = adam->lr * adam->weight_decay;
-  a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
-  if (p->persistent) {
-    MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
-  } else {
-    // The device compacts the tile list to the tensors that are active (mask) and have gradients;
-    // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles.
-    uint64_t bound = 0;
-    for (uint32_t t = 0; t < h.n_tensors; ++t)
-      if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
-    if (bound == 0) bound = 1;
-    MOEV_HIP(moev::launch_active_scan(a, p->d_active_tile_start, s));
-    a.tile_start = p->d_active_tile_start;
-    MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
-                                      static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
-  }
-  return MOEV_OK;
+  return launch_replay_locked(p, adam, d_active_mask, grads, state, s, fused ? static_cast<int>(slot) : -1, d_packed);
 }
 
 }  // extern "C"

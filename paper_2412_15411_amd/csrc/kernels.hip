@@ -323,7 +323,8 @@ __global__ __launch_bounds__(T) void k_unpack_direct(MOEV_COPY_TABLES, const uin
     return;
   }
   if (blockIdx.x == 0) update_mask<T>(a);
-  if (blockIdx.x < tile_start[a.n_seg]) unpack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, blockIdx.x);
+  const uint32_t tile = blockIdx.x + a.tile_begin;
+  if (tile < tile_start[a.n_seg]) unpack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, tile);
 }
 
 // ---- fixed grid walking the tile list, map staged in LDS ----
@@ -397,25 +398,22 @@ __device__ __forceinline__ void adam_element(float& p, float& m, float& v, float
       const uint32_t *__restrict__ op_of_tensor, const uint8_t *__restrict__ mask,                    \
       void *const *__restrict__ ptrs, void *const *__restrict__ grads
 
-// Elements [begin, end) of tensor t; begin is a multiple of four.
+// Elements [begin, end) of one tensor; begin is a multiple of four.  The old state is read from
+// Ps, Ms, Vs (the dense tensors themselves, or their copies inside a packed snapshot) and the new
+// state is written to P, M, V, C.
 template <uint32_t T, uint32_t U, bool NT>
-__device__ __forceinline__ void adam_range(const AdamArgs& a, void* const* __restrict__ ptrs,
-                                           void* const* __restrict__ grads, uint32_t t, uint64_t begin, uint64_t end,
-                                           const AdamConst& c) {
-  float* __restrict__ P = static_cast<float*>(ptrs[t]);
-  float* __restrict__ M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
-  float* __restrict__ V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
-  uint16_t* __restrict__ C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
-  const float* __restrict__ G = static_cast<const float*>(grads[t]);
+__device__ __forceinline__ void adam_range(const float* Ps, const float* Ms, const float* Vs,
+                                           const float* __restrict__ G, float* P, float* M, float* V,
+                                           uint16_t* __restrict__ C, uint64_t begin, uint64_t end, const AdamConst& c) {
   for (uint64_t base = begin + 4ull * threadIdx.x; base < end; base += 4ull * T * U) {
     f32x4 p[U], m[U], v[U], g[U];
 #pragma unroll
     for (uint32_t u = 0; u < U; ++u) {
       const uint64_t i = base + 4ull * T * u;
       if (i + 4 <= end) {
-        p[u] = ld<NT>(reinterpret_cast<const f32x4*>(P + i));
-        m[u] = ld<NT>(reinterpret_cast<const f32x4*>(M + i));
-        v[u] = ld<NT>(reinterpret_cast<const f32x4*>(V + i));
+        p[u] = ld<NT>(reinterpret_cast<const f32x4*>(Ps + i));
+        m[u] = ld<NT>(reinterpret_cast<const f32x4*>(Ms + i));
+        v[u] = ld<NT>(reinterpret_cast<const f32x4*>(Vs + i));
         g[u] = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
       }
     }
@@ -439,7 +437,7 @@ __device__ __forceinline__ void adam_range(const AdamArgs& a, void* const* __res
       } else if (i < end) {
         // ragged tail of a tensor whose length is not a multiple of four
         for (uint64_t e = i; e < end; ++e) {
-          float pe = ld<false>(P + e), me = ld<false>(M + e), ve = ld<false>(V + e);
+          float pe = ld<false>(Ps + e), me = ld<false>(Ms + e), ve = ld<false>(Vs + e);
           adam_element(pe, me, ve, ld<false>(G + e), c);
           st<false>(P + e, pe);
           st<false>(M + e, me);
@@ -462,7 +460,44 @@ __global__ __launch_bounds__(T) void k_adam_direct(MOEV_ADAM_TABLES, const AdamA
   const uint64_t end = begin + a.tile_elems < numel ? begin + a.tile_elems : numel;
   (void)op_of_tensor;
   (void)mask;
-  adam_range<T, U, NT>(a, ptrs, grads, t, begin, end, adam_const(a));
+  float* P = static_cast<float*>(ptrs[t]);
+  float* M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
+  float* V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
+  uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
+  adam_range<T, U, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a));
+}
+
+// Fused snapshot load + replay (steps 1+2, 3+4, 5+6 of the Sec. 3.3 walk-through in one pass): for
+// the tensors whose FP32 state the snapshot carries, the old state is read straight from the packed
+// buffer instead of being scattered to the dense tensors first and read back.
+template <uint32_t T, uint32_t U, bool NT>
+__global__ __launch_bounds__(T) void k_adam_fused(MOEV_ADAM_TABLES, const uint64_t* __restrict__ src_off,
+                                                  const uint64_t* __restrict__ header, const AdamArgs a) {
+  bool ok = true;
+#pragma unroll
+  for (uint32_t k = 0; k < 7; ++k)
+    if (k != 3 && header[k] != a.header[k]) ok = false;
+  if (!ok) return;  // foreign snapshot: the unpack launch in front of this one has raised the status word
+  const uint32_t tile = blockIdx.x;
+  if (tile >= tile_start[a.n_tensors]) return;
+  const uint32_t t = owner_of_tile(tile_start, a.n_tensors, tile);
+  const uint64_t numel = numel_of[t];
+  const uint64_t begin = static_cast<uint64_t>(tile - tile_start[t]) * a.tile_elems;
+  const uint64_t end = begin + a.tile_elems < numel ? begin + a.tile_elems : numel;
+  (void)op_of_tensor;
+  (void)mask;
+  float* P = static_cast<float*>(ptrs[t]);
+  float* M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
+  float* V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
+  uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
+  const float *Ps = P, *Ms = M, *Vs = V;
+  const uint64_t op = src_off[t];
+  if (op != ~0ull) {
+    Ps = reinterpret_cast<const float*>(a.packed + op);
+    Ms = reinterpret_cast<const float*>(a.packed + src_off[static_cast<uint64_t>(a.n_tensors) + t]);
+    Vs = reinterpret_cast<const float*>(a.packed + src_off[2ull * a.n_tensors + t]);
+  }
+  adam_range<T, U, NT>(Ps, Ms, Vs, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a));
 }
 
 // fixed grid over the static (all tensors) tile list; frozen tensors are jumped over
@@ -488,7 +523,11 @@ __global__ __launch_bounds__(kThreads) void k_adam_persistent(MOEV_ADAM_TABLES, 
     const uint64_t numel = numel_of[t];
     const uint64_t begin = static_cast<uint64_t>(tile - start[t]) * a.tile_elems;
     const uint64_t end = begin + a.tile_elems < numel ? begin + a.tile_elems : numel;
-    adam_range<kThreads, 2, NT>(a, ptrs, grads, t, begin, end, c);
+    float* P = static_cast<float*>(ptrs[t]);
+    float* M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
+    float* V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
+    uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
+    adam_range<kThreads, 2, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, c);
     tile += gridDim.x;
   }
 }
@@ -575,6 +614,14 @@ hipError_t launch_unpack_direct(const CopyArgs& a, uint32_t blocks, uint32_t thr
 hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
                               hipStream_t s) {
   MOEV_DIRECT_ALL(k_adam_direct)
+}
+#undef MOEV_LAUNCH_ARGS
+
+#define MOEV_LAUNCH_ARGS \
+  a.tile_start, a.numel, a.op_of_tensor, a.mask, a.ptrs, a.grads, a.src_off, reinterpret_cast<const uint64_t*>(a.packed), a
+hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                             hipStream_t s) {
+  MOEV_DIRECT_ALL(k_adam_fused)
 }
 #undef MOEV_LAUNCH_ARGS
 

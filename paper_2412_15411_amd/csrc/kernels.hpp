@@ -43,6 +43,7 @@ struct CopyArgs {
   const uint32_t* slot_of_op;
   uint32_t* status;
   uint32_t n_ops, slot, derive_compute;
+  uint32_t tile_begin;         // first tile of the launch (unpack of the compute-weight segments only)
 };
 
 struct AdamArgs {
@@ -53,6 +54,10 @@ struct AdamArgs {
   void* const* ptrs;           // [4 * n_tensors] master, m, v, compute
   void* const* grads;          // [n_tensors]
   uint32_t* status;            // raised when an active operator has no gradient pointer
+  // fused load-and-replay only: FP32 state of the newly active tensors is read from the snapshot
+  const uint64_t* src_off;     // [3 * n_tensors] offsets of master, m, v in `packed`, ~0 = read the dense tensor
+  const uint8_t* packed;
+  uint64_t header[7];
   uint32_t n_tensors, tile_elems, lds_entries, has_decay;
   float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
 };
@@ -70,6 +75,8 @@ hipError_t launch_unpack_direct(const CopyArgs& a, uint32_t blocks, uint32_t thr
 hipError_t launch_active_scan(const AdamArgs& a, uint32_t* d_out, hipStream_t s);
 hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
                               hipStream_t s);
+hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                             hipStream_t s);
 
 // fixed grid of 256-thread workgroups walking the tile list
 hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);

@@ -403,7 +403,7 @@ def test_adam_special_values(orc, dev):
 # ---------------------------------------------------------------------------------------
 # whole window: snapshots during a dense run, then sparse-to-dense conversion
 # ---------------------------------------------------------------------------------------
-def _gpu_window(orc, dev, wl, seed, align=256, via_host=False, **tune):
+def _gpu_window(orc, dev, wl, seed, align=256, via_host=False, fused=False, **tune):
     """Dense GPU run with per-iteration snapshots, then GPU conversion from them; returns the GPU's
     converted state, the oracle's dense-run state and the oracle's snapshots."""
     model, hp = model_of(wl, align=align), hp_of(wl)
@@ -436,40 +436,78 @@ def _gpu_window(orc, dev, wl, seed, align=256, via_host=False, **tune):
         if via_host:
             host = bufs[i].cpu().pin_memory()
             bufs[i].fill_(0)
-        B.restore_unpack(plan, i, host, bufs[i], rebuilt.state, mask)
-        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + i + 1, mask,
-                         grads_dev[wl.t0 + i + 1], rebuilt.state)
+        if fused:
+            # frozen operators have no gradients; the fused call reads the new operators' FP32 state from the snapshot
+            g = [x if wl.slot_of_op[wl.tensors[t][0]] <= i else None for t, x in enumerate(grads_dev[wl.t0 + i + 1])]
+            B.convert_window_step(plan, i, host, bufs[i], wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay,
+                                  wl.t0 + i + 1, mask, g, rebuilt.state)
+        else:
+            B.restore_unpack(plan, i, host, bufs[i], rebuilt.state, mask)
+            B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + i + 1, mask,
+                             grads_dev[wl.t0 + i + 1], rebuilt.state)
         torch.cuda.synchronize()
     B.ckpt_plan_device_status(plan)
     assert mask.all().item()
     return rebuilt, live, dense
 
 
-def test_window_tiny_config(orc, dev):
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
+def test_window_tiny_config(orc, dev, fused):
     """configs[0]: snapshots bit-exact, converted state == the GPU's own dense run bitwise and
     within 1e-6 relative of the oracle's brute-force dense Adam run."""
     wl = W.tiny_moe()
-    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=0)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=0, fused=fused)
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "c0")
     assert rebuilt.guards_intact() and live.guards_intact()
 
 
-def test_window_conversion_stress_small(orc, dev):
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
+def test_window_conversion_stress_small(orc, dev, fused):
     """A shrunken configs[4]: 2 layers x (16 routed + 2 shared), W = 8, permuted schedule, heavy-tailed
     gradients, restore through pinned host memory."""
     wl = W.conversion_stress(n_layers=2, n_routed=16, n_shared=2, d_model=64, d_ff=44, per_slot=2)
     assert wl.window == 8
-    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=4, via_host=True, tile=4096, adam_tile=1024)
+    tune = {} if fused else dict(tile=4096, adam_tile=1024)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=4, via_host=True, fused=fused, **tune)
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "c4-small")
 
 
-def test_window_ragged_direct_shapes(orc, dev):
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
+def test_window_ragged_direct_shapes(orc, dev, fused):
     wl = ragged_workload(78, n_ops=9, window=3, with_empty=True)
-    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=6, align=64, copy_shape=(512, 2), adam_shape=(128, 1))
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=6, align=64, fused=fused, copy_shape=(512, 2), adam_shape=(128, 1))
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "ragged-window-direct")
+    assert rebuilt.guards_intact()
+
+
+def test_fused_step_refuses_foreign_snapshot_and_missing_gradients(orc, dev):
+    """The fused step modifies nothing when the device-resident snapshot is not the slot's, and
+    insists on gradients for the operators it activates."""
+    wl = ragged_workload(33)
+    model, plan = model_of(wl), make_plan(wl)
+    st_cpu = W.make_state(wl, seed=2)
+    ds = DeviceState(st_cpu, dev)
+    before = ds.to_oracle()
+    snap = orc.pack(model, 1, 5, state_of(st_cpu))
+    buf = packed_buffer(plan, dev)
+    buf.zero_()
+    buf[:snap.size].copy_(torch.from_numpy(snap))
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    grads = [g.to(dev) for g in W.make_grads(wl, 6, seed=2)]
+    B.convert_window_step(plan, 2, None, buf, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, 6, mask, grads, ds.state)
+    torch.cuda.synchronize()
+    with pytest.raises(B.MoevError) as e:
+        B.ckpt_plan_device_status(plan)
+    assert e.value.code == B.E_MISMATCH
+    assert states_equal(ds.to_oracle(), before) == [] and not mask.any().item() and ds.guards_intact()
+    first_active = next(t for t, (op, n) in enumerate(wl.tensors) if wl.slot_of_op[op] == 1 and n)
+    grads[first_active] = None
+    with pytest.raises(B.MoevError) as e:
+        B.convert_window_step(plan, 1, None, buf, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, 6, mask, grads, ds.state)
+    assert e.value.code == B.E_INVAL
 
 
 def test_window_ragged_small_grid(orc, dev):
