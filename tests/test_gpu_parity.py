@@ -213,6 +213,70 @@ def test_unpack_bit_exact_with_sentinels(orc, dev, seed, align, tile, blocks, sh
         assert np.array_equal(mask.cpu().numpy(), ref_mask)
 
 
+@pytest.mark.parametrize("persistent", [False, True], ids=["direct", "fixed_grid_global_table"])
+def test_pack_unpack_many_tiny_segments(orc, dev, persistent):
+    """18,000 segments in a slot (beyond what the fixed-grid shape stages in LDS): every tensor is a
+    few elements long, so nearly every tile is a ragged tail."""
+    wl = _many_segments()
+    model = model_of(wl, align=16)
+    st_cpu = W.random_bits_state(wl, seed=3)
+    ref_state = state_of(st_cpu)
+    ds = DeviceState(st_cpu, dev)
+    plan = make_plan(wl, align=16, tile=4096 if persistent else None, blocks=64 if persistent else None)
+    buf = packed_buffer(plan, dev)
+    for k in range(wl.window):
+        buf.fill_(0xA5)
+        B.snapshot_pack(plan, k, 3, ds.state, buf)
+        torch.cuda.synchronize()
+        exp = orc.pack(model, k, 3, ref_state)
+        assert buf.cpu().numpy()[:exp.size].tobytes() == exp.tobytes()
+        target = DeviceState(st_cpu, dev)
+        target.poison()
+        ref = target.to_oracle()
+        ref_mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        orc.unpack(model, k, exp, ref, ref_mask)
+        mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+        B.restore_unpack(plan, k, None, buf, target.state, mask)
+        torch.cuda.synchronize()
+        assert states_equal(target.to_oracle(), ref) == [] and target.guards_intact()
+        assert np.array_equal(mask.cpu().numpy(), ref_mask)
+
+
+def test_degenerate_slots(orc, dev):
+    """Slots with no active operator (only compute weights), with nothing at all (header only), a
+    window of one slot (dense checkpoint) and an alignment above the header size."""
+    cases = [
+        W.Workload("gap", [(0, 5000), (1, 33), (2, 70001)], [0, 3, 3], 5),      # slots 1, 2 compute-only; 4 empty
+        W.Workload("dense", [(0, 4097), (1, 12)], [0, 0], 1),
+    ]
+    for wl in cases:
+        for align in (16, 4096):
+            model, plan = model_of(wl, align=align), make_plan(wl, align=align)
+            st_cpu = W.random_bits_state(wl, seed=8)
+            ref_state = state_of(st_cpu)
+            ds = DeviceState(st_cpu, dev)
+            buf = packed_buffer(plan, dev)
+            for k in range(wl.window):
+                buf.fill_(0xA5)
+                B.snapshot_pack(plan, k, 9, ds.state, buf)
+                torch.cuda.synchronize()
+                exp = orc.pack(model, k, 9, ref_state)
+                got = buf.cpu().numpy()
+                assert got[:exp.size].tobytes() == exp.tobytes(), (wl.name, align, k)
+                assert (got[exp.size:] == 0xA5).all()
+                target = DeviceState(st_cpu, dev)
+                target.poison()
+                ref = target.to_oracle()
+                ref_mask = np.full(wl.n_ops, 5, dtype=np.uint8)
+                orc.unpack(model, k, exp, ref, ref_mask)
+                mask = torch.full((wl.n_ops,), 5, dtype=torch.uint8, device=dev)
+                B.restore_unpack(plan, k, None, buf, target.state, mask)
+                torch.cuda.synchronize()
+                B.ckpt_plan_device_status(plan)
+                assert states_equal(target.to_oracle(), ref) == [] and target.guards_intact()
+                assert np.array_equal(mask.cpu().numpy(), ref_mask)
+
+
 def test_pack_drain_restore_roundtrip_through_pinned_host(orc, dev):
     """pack -> drain (side stream, event-ordered) -> host bytes equal the oracle's snapshot;
     restore from the pinned copy (H2D + scatter) brings a poisoned state back: identity."""
