@@ -169,6 +169,25 @@ int moev_order_operators(uint32_t n_ops, const double *popularity, uint32_t *ord
 int moev_reorder_needed(uint32_t n_ops, const double *old_freq, const double *new_freq,
                         double rel_change, double min_fraction);
 
+/* App. B alternatives to the hard activation count, to be fed to moev_order_operators:
+ * time-decayed popularity out = alpha * previous + (1 - alpha) * batch_count (exponential moving
+ * average over mini-batches), and capacity-aware popularity out = popularity / capacity.
+ * (Soft-count popularity is the sum of gating probabilities: the caller's own reduction.)
+ * `out` may alias `previous` / `popularity`.  MOEV_E_INVAL on null pointers, alpha outside [0, 1] or
+ * a non-positive capacity. */
+int moev_popularity_time_decayed(uint32_t n_ops, double alpha, const double *previous, const double *batch_count,
+                                 double *out);
+int moev_popularity_capacity_aware(uint32_t n_ops, const double *popularity, const double *capacity, double *out);
+
+/* Efficiency model.  Sec. 2.4 / App. C: ETTR = 1/(1 + T_ckpt/(T_iter*interval)) * 1/(1 + E[R]/MTBF);
+ * returns NaN on non-positive t_iter_s, interval or mtbf_s.  Sec. 3.6: expected and worst-case
+ * recovery time; sparse = 0: dense checkpoint every `interval_or_window` iterations (E[R] = half the
+ * interval, worst = the interval); sparse = 1: sparse window of that many iterations (E[R] = 3/2 W
+ * T_iter, worst = 2 W T_iter). */
+double moev_ettr(double t_ckpt_s, double t_iter_s, double ckpt_interval_iters, double expected_recovery_s,
+                 double mtbf_s);
+int moev_recovery_time(int sparse, double interval_or_window, double t_iter_s, double *expected_s, double *worst_s);
+
 /* queries (host) */
 uint32_t ckpt_plan_window(const moev_plan *plan);
 uint32_t ckpt_plan_n_ops(const moev_plan *plan);

@@ -203,6 +203,38 @@ def check_schedule(order, slot_of_op, window) -> int:
     return lib().orc_check_schedule(C.c_uint32(n), o, s, C.c_uint32(window))
 
 
+def popularity_time_decayed(alpha, previous, batch_count):
+    n = len(previous)
+    out = (C.c_double * n)()
+    lib().orc_popularity_time_decayed(C.c_uint32(n), C.c_double(alpha), (C.c_double * n)(*previous),
+                                      (C.c_double * n)(*batch_count), out)
+    return list(out)
+
+
+def popularity_capacity_aware(popularity, capacity):
+    n = len(popularity)
+    out = (C.c_double * n)()
+    lib().orc_popularity_capacity_aware(C.c_uint32(n), (C.c_double * n)(*popularity), (C.c_double * n)(*capacity), out)
+    return list(out)
+
+
+def ettr(t_ckpt, t_iter, ckpt_interval, expected_recovery, mtbf):
+    f = lib().orc_ettr
+    f.restype = C.c_double
+    f.argtypes = [C.c_double] * 5
+    return f(t_ckpt, t_iter, ckpt_interval, expected_recovery, mtbf)
+
+
+def recovery(kind, interval_or_window, t_iter):
+    """kind = 'dense' or 'sparse' -> (expected, worst) recovery time in seconds (Sec. 3.6)."""
+    e, w = C.c_double(), C.c_double()
+    f = lib().orc_recovery_dense if kind == "dense" else lib().orc_recovery_sparse
+    f.restype = None
+    f.argtypes = [C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    f(interval_or_window, t_iter, C.byref(e), C.byref(w))
+    return e.value, w.value
+
+
 # --------------------------------------------------------------------------------------
 # layout / pack / unpack
 # --------------------------------------------------------------------------------------

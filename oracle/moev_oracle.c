@@ -100,6 +100,43 @@ int orc_check_schedule(uint32_t n_ops, const uint32_t *order, const uint32_t *sl
   return ORC_OK;
 }
 
+/*
+ * App. B, time-decayed popularity: an exponential moving average over mini-batches,
+ *   A(t) = alpha * A(t-1) + (1 - alpha) * (number of tokens of batch t routed to the expert).
+ */
+void orc_popularity_time_decayed(uint32_t n_ops, double alpha, const double *previous, const double *batch_count,
+                                 double *out) {
+  for (uint32_t e = 0; e < n_ops; ++e) out[e] = alpha * previous[e] + (1.0 - alpha) * batch_count[e];
+}
+
+/* App. B, capacity-aware ordering: popularity divided by the expert's capacity factor. */
+void orc_popularity_capacity_aware(uint32_t n_ops, const double *popularity, const double *capacity, double *out) {
+  for (uint32_t e = 0; e < n_ops; ++e) out[e] = popularity[e] / capacity[e];
+}
+
+/*
+ * Sec. 2.4 (and App. C): ETTR ~ 1 / (1 + T_ckpt / (T_iter * Ckpt_interval)) * 1 / (1 + E[R] / MTBF),
+ * runtime overhead of checkpointing times recovery overhead under Poisson failures.
+ */
+double orc_ettr(double t_ckpt, double t_iter, double ckpt_interval, double expected_recovery, double mtbf) {
+  double runtime_overhead = t_ckpt / (t_iter * ckpt_interval);
+  double recovery_overhead = expected_recovery / mtbf;
+  return 1.0 / (1.0 + runtime_overhead) * (1.0 / (1.0 + recovery_overhead));
+}
+
+/* Sec. 3.6, dense checkpointing: 0 <= R <= interval * T_iter, E[R] ~ interval * T_iter / 2. */
+void orc_recovery_dense(double ckpt_interval, double t_iter, double *expected, double *worst) {
+  *worst = ckpt_interval * t_iter;
+  *expected = 0.5 * ckpt_interval * t_iter;
+}
+
+/* Sec. 3.6, sparse checkpointing: replay W_sparse iterations to rebuild the dense checkpoint, then
+ * re-execute up to W_sparse more: 0 <= R <= 2 * W * T_iter, E[R] ~ 3/2 * W * T_iter. */
+void orc_recovery_sparse(double w_sparse, double t_iter, double *expected, double *worst) {
+  *worst = 2.0 * w_sparse * t_iter;
+  *expected = 1.5 * w_sparse * t_iter;
+}
+
 /* ===================================================================================
  * Snapshot layout, pack, unpack -- Sec. 3.2 (what a sparse snapshot holds), Sec. 3.3
  * (what loading one does).  The byte layout of a packed snapshot is this build's own

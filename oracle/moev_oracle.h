@@ -83,6 +83,14 @@ int orc_order_by_popularity(uint32_t n_ops, const double *popularity, uint32_t *
 int orc_check_schedule(uint32_t n_ops, const uint32_t *order, const uint32_t *slot_of_op,
                        uint32_t window);
 
+/* ---- alternative popularity estimates (App. B) and the efficiency model (Sec. 2.4, Sec. 3.6) --- */
+void orc_popularity_time_decayed(uint32_t n_ops, double alpha, const double *previous, const double *batch_count,
+                                 double *out);
+void orc_popularity_capacity_aware(uint32_t n_ops, const double *popularity, const double *capacity, double *out);
+double orc_ettr(double t_ckpt, double t_iter, double ckpt_interval, double expected_recovery, double mtbf);
+void orc_recovery_dense(double ckpt_interval, double t_iter, double *expected, double *worst);
+void orc_recovery_sparse(double w_sparse, double t_iter, double *expected, double *worst);
+
 /* ---- snapshot layout, pack, unpack (Sec. 3.2, Sec. 3.3) ---------------------------- */
 uint64_t orc_plan_hash(const orc_model *mdl);
 int64_t orc_layout(const orc_model *mdl, uint32_t slot, orc_segment *segs, uint64_t seg_cap,

@@ -24,7 +24,8 @@ HEADER_BYTES = 256
 
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",
-    "moev_reorder_needed", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
+    "moev_reorder_needed", "moev_popularity_time_decayed", "moev_popularity_capacity_aware", "moev_ettr",
+    "moev_recovery_time", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
     "ckpt_plan_hash", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
@@ -85,6 +86,12 @@ def _load():
                                           C.POINTER(u32), C.POINTER(u32)]
     lib.moev_order_operators.argtypes = [u32, C.POINTER(C.c_double), C.POINTER(u32)]
     lib.moev_reorder_needed.argtypes = [u32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double, C.c_double]
+    dp = C.POINTER(C.c_double)
+    lib.moev_popularity_time_decayed.argtypes = [u32, C.c_double, dp, dp, dp]
+    lib.moev_popularity_capacity_aware.argtypes = [u32, dp, dp, dp]
+    lib.moev_ettr.argtypes = [C.c_double] * 5
+    lib.moev_ettr.restype = C.c_double
+    lib.moev_recovery_time.argtypes = [C.c_int, C.c_double, C.c_double, dp, dp]
     for name in ("ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active"):
         getattr(lib, name).argtypes = [vp]
         getattr(lib, name).restype = u32
@@ -186,6 +193,30 @@ def moev_reorder_needed(old_freq: Sequence[float], new_freq: Sequence[float], re
     n = len(old_freq)
     return bool(_check(_lib.moev_reorder_needed(n, (C.c_double * n)(*old_freq), (C.c_double * n)(*new_freq),
                                                 rel_change, min_fraction)))
+
+
+def moev_popularity_time_decayed(alpha: float, previous: Sequence[float], batch_count: Sequence[float]) -> List[float]:
+    n = len(previous)
+    out = (C.c_double * n)()
+    _check(_lib.moev_popularity_time_decayed(n, alpha, (C.c_double * n)(*previous), (C.c_double * n)(*batch_count), out))
+    return list(out)
+
+
+def moev_popularity_capacity_aware(popularity: Sequence[float], capacity: Sequence[float]) -> List[float]:
+    n = len(popularity)
+    out = (C.c_double * n)()
+    _check(_lib.moev_popularity_capacity_aware(n, (C.c_double * n)(*popularity), (C.c_double * n)(*capacity), out))
+    return list(out)
+
+
+def moev_ettr(t_ckpt_s, t_iter_s, ckpt_interval_iters, expected_recovery_s, mtbf_s) -> float:
+    return _lib.moev_ettr(t_ckpt_s, t_iter_s, ckpt_interval_iters, expected_recovery_s, mtbf_s)
+
+
+def moev_recovery_time(sparse: bool, interval_or_window: float, t_iter_s: float):
+    e, w = C.c_double(), C.c_double()
+    _check(_lib.moev_recovery_time(int(bool(sparse)), interval_or_window, t_iter_s, C.byref(e), C.byref(w)))
+    return e.value, w.value
 
 
 # ---- plan --------------------------------------------------------------------------------

@@ -557,6 +557,44 @@ int moev_reorder_needed(uint32_t n_ops, const double* old_freq, const double* ne
   return static_cast<double>(moved) >= min_fraction * static_cast<double>(n_ops) ? 1 : 0;
 }
 
+// App. B: exponential moving average of the per-batch activation counts.
+int moev_popularity_time_decayed(uint32_t n_ops, double alpha, const double* previous, const double* batch_count,
+                                 double* out) {
+  if (!previous || !batch_count || !out || !(alpha >= 0.0 && alpha <= 1.0))
+    return fail(MOEV_E_INVAL, "moev_popularity_time_decayed: null pointer or alpha outside [0, 1]");
+  const double fresh = 1.0 - alpha;
+  for (uint32_t e = 0; e < n_ops; ++e) out[e] = alpha * previous[e] + fresh * batch_count[e];
+  return MOEV_OK;
+}
+
+// App. B: utilisation relative to capacity.
+int moev_popularity_capacity_aware(uint32_t n_ops, const double* popularity, const double* capacity, double* out) {
+  if (!popularity || !capacity || !out) return fail(MOEV_E_INVAL, "moev_popularity_capacity_aware: null pointer");
+  for (uint32_t e = 0; e < n_ops; ++e)
+    if (!(capacity[e] > 0.0)) return fail(MOEV_E_INVAL, "moev_popularity_capacity_aware: capacity %u is not positive", e);
+  for (uint32_t e = 0; e < n_ops; ++e) out[e] = popularity[e] / capacity[e];
+  return MOEV_OK;
+}
+
+// Sec. 2.4: product of the fault-free efficiency and the efficiency under failures.
+double moev_ettr(double t_ckpt_s, double t_iter_s, double ckpt_interval_iters, double expected_recovery_s,
+                 double mtbf_s) {
+  if (!(t_iter_s > 0.0) || !(ckpt_interval_iters > 0.0) || !(mtbf_s > 0.0)) return std::nan("");
+  const double useful_fault_free = (t_iter_s * ckpt_interval_iters) / (t_iter_s * ckpt_interval_iters + t_ckpt_s);
+  const double useful_under_failures = mtbf_s / (mtbf_s + expected_recovery_s);
+  return useful_fault_free * useful_under_failures;
+}
+
+// Sec. 3.6
+int moev_recovery_time(int sparse, double interval_or_window, double t_iter_s, double* expected_s, double* worst_s) {
+  if (!expected_s || !worst_s || !(interval_or_window > 0.0) || !(t_iter_s > 0.0))
+    return fail(MOEV_E_INVAL, "moev_recovery_time: bad argument");
+  const double span = interval_or_window * t_iter_s;
+  *expected_s = sparse ? span + 0.5 * span : 0.5 * span;  // conversion replays W, then on average half a window more
+  *worst_s = sparse ? span + span : span;
+  return MOEV_OK;
+}
+
 uint32_t ckpt_plan_window(const moev_plan* p) { return p ? p->host.window : 0; }
 uint32_t ckpt_plan_n_ops(const moev_plan* p) { return p ? p->host.n_ops : 0; }
 uint32_t ckpt_plan_n_tensors(const moev_plan* p) { return p ? p->host.n_tensors : 0; }
