@@ -39,7 +39,7 @@
  *   offsets: first segment at roundup(256, align); each next one roundup(nbytes, align)
  *           further; padding bytes are zero.
  *   plan hash: 64-bit FNV-1a over u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 element
- *           widths (master, optimizer, compute), per tensor (u32 op, u64 numel), per operator
+ *           widths (master, m, v, compute), per tensor (u32 op, u64 numel), per operator
  *           u32 slot, per position u32 order.
  */
 #ifndef MOEV_H
@@ -93,9 +93,10 @@ typedef struct {
   double t_iter_s;             /* AUTO: T_Iter */
   double host_link_Bps;        /* AUTO: B_PCIe, bytes per second */
   uint32_t align;              /* segment alignment in the packed buffer: power of two >= 16; 0 = 256 */
-  uint8_t master_bytes;        /* element widths; 0 = defaults 4, 4, 2 */
-  uint8_t opt_bytes_each;
-  uint8_t compute_bytes;
+  uint8_t master_bytes;        /* element widths in bytes (1, 2, 4 or 8); 0 = defaults 4, 4, 4, 2.  Other */
+  uint8_t m_bytes;             /* values describe the low-precision regimes of Sec. 5.6 (e.g. FP8 master, */
+  uint8_t v_bytes;             /* FP8 + FP16 moments, FP8 compute = 1, 1, 2, 1): pack, drain and unpack */
+  uint8_t compute_bytes;       /* are byte copies and work for any widths; the replay needs 4, 4, 4, 2 */
 } moev_plan_cfg;
 
 typedef struct {

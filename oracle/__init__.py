@@ -41,7 +41,7 @@ class _Tensor(C.Structure):
 
 
 class _Widths(C.Structure):
-    _fields_ = [("master", C.c_uint32), ("opt", C.c_uint32), ("compute", C.c_uint32)]
+    _fields_ = [("master", C.c_uint32), ("m", C.c_uint32), ("v", C.c_uint32), ("compute", C.c_uint32)]
 
 
 class _Segment(C.Structure):
@@ -101,7 +101,7 @@ class Model:
     slot_of_op: Sequence[int]
     window: int
     align: int = 256
-    widths: Tuple[int, int, int] = (4, 4, 2)  # bytes per element: master, each Adam moment, compute
+    widths: Tuple[int, ...] = (4, 4, 4, 2)   # bytes per element: master, Adam m, Adam v, compute
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -117,8 +117,10 @@ class Model:
         order = (C.c_uint32 * self.n_ops)(*[int(x) for x in self.order])
         slots = (C.c_uint32 * self.n_ops)(*[int(x) for x in self.slot_of_op])
         self._keep = [ts, order, slots]
-        return _Model(self.n_ops, self.n_tensors, ts, order, slots, int(self.window), int(self.align),
-                      _Widths(*[int(w) for w in self.widths]))
+        w = tuple(int(x) for x in self.widths)
+        if len(w) == 3:  # (master, both moments, compute)
+            w = (w[0], w[1], w[1], w[2])
+        return _Model(self.n_ops, self.n_tensors, ts, order, slots, int(self.window), int(self.align), _Widths(*w))
 
 
 @dataclass

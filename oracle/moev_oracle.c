@@ -158,7 +158,8 @@ void orc_recovery_sparse(double w_sparse, double t_iter, double *expected, doubl
 static uint32_t width_of(const orc_model *mdl, uint32_t kind) {
   if (kind == ORC_MASTER) return mdl->width.master;
   if (kind == ORC_COMPUTE) return mdl->width.compute;
-  return mdl->width.opt;
+  if (kind == ORC_ADAM_M) return mdl->width.m;
+  return mdl->width.v;
 }
 
 static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -184,7 +185,7 @@ static uint64_t fnv1a(uint64_t h, uint64_t value, int nbytes) {
 /*
  * Identity of a plan, stored in every snapshot header so that a snapshot is never loaded
  * into a model or schedule it was not taken from.  64-bit FNV-1a over the little-endian
- * stream: u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 widths (master, opt,
+ * stream: u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 widths (master, m, v,
  * compute), then per tensor (u32 op, u64 numel), per operator u32 slot, per position
  * u32 order.
  */
@@ -195,7 +196,8 @@ uint64_t orc_plan_hash(const orc_model *mdl) {
   h = fnv1a(h, mdl->window, 4);
   h = fnv1a(h, mdl->align, 4);
   h = fnv1a(h, mdl->width.master, 1);
-  h = fnv1a(h, mdl->width.opt, 1);
+  h = fnv1a(h, mdl->width.m, 1);
+  h = fnv1a(h, mdl->width.v, 1);
   h = fnv1a(h, mdl->width.compute, 1);
   for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
     h = fnv1a(h, mdl->tensors[t].op, 4);
@@ -416,7 +418,7 @@ void orc_adam_tensor(float *p, float *m, float *v, const float *g, uint16_t *c, 
 int orc_replay_step(const orc_model *mdl, const orc_adam_hp *hp, uint64_t step,
                     const uint8_t *active_mask, const float *const *grads, const orc_state *st) {
   if (!mdl || !hp || !active_mask || !grads || !st || step == 0) return ORC_BAD_ARG;
-  if (mdl->width.master != 4 || mdl->width.opt != 4 || mdl->width.compute != 2) return ORC_BAD_ARG;
+  if (mdl->width.master != 4 || mdl->width.m != 4 || mdl->width.v != 4 || mdl->width.compute != 2) return ORC_BAD_ARG;
   for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
     if (!active_mask[mdl->tensors[t].op]) continue;
     orc_adam_tensor((float *)st->master[t], (float *)st->m[t], (float *)st->v[t], grads[t],

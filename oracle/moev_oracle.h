@@ -39,9 +39,10 @@ typedef struct {
 } orc_tensor;
 
 /* element width in bytes of each kind (FP32 master + FP32 Adam moments + 2-byte compute
- * weights is the paper's default regime: 12 vs 2 bytes per parameter, Sec. 3.2) */
+ * weights is the paper's default regime: 12 vs 2 bytes per parameter, Sec. 3.2; the
+ * low-precision regimes of Sec. 5.6 use other widths, e.g. FP8 master + FP8/FP16 moments) */
 typedef struct {
-  uint32_t master, opt, compute;
+  uint32_t master, m, v, compute;
 } orc_widths;
 
 typedef struct {

@@ -49,7 +49,7 @@ class _PlanCfg(C.Structure):
                 ("mode", C.c_int), ("window", C.c_uint32), ("n_active", C.c_uint32),
                 ("order", C.POINTER(C.c_uint32)), ("slot_of_op", C.POINTER(C.c_uint32)),
                 ("t_iter_s", C.c_double), ("host_link_Bps", C.c_double), ("align", C.c_uint32),
-                ("master_bytes", C.c_uint8), ("opt_bytes_each", C.c_uint8), ("compute_bytes", C.c_uint8)]
+                ("master_bytes", C.c_uint8), ("m_bytes", C.c_uint8), ("v_bytes", C.c_uint8), ("compute_bytes", C.c_uint8)]
 
 
 class _Segment(C.Structure):
@@ -235,15 +235,17 @@ class Plan:
 def ckpt_plan(tensors: Sequence, mode: int = EXPLICIT, window: int = 0, n_active: int = 0,
               order: Optional[Sequence[int]] = None, slot_of_op: Optional[Sequence[int]] = None,
               t_iter_s: float = 0.0, host_link_Bps: float = 0.0, align: int = 0,
-              widths=(0, 0, 0), n_ops: Optional[int] = None) -> Plan:
+              widths=(0, 0, 0, 0), n_ops: Optional[int] = None) -> Plan:
     nt = len(tensors)
     if n_ops is None:
         n_ops = (max(op for op, _ in tensors) + 1) if nt else 0
     ts = (_Tensor * max(nt, 1))(*[_Tensor(int(o), int(n)) for o, n in tensors])
     order_a = (C.c_uint32 * len(order))(*order) if order is not None else None
     slots_a = (C.c_uint32 * len(slot_of_op))(*slot_of_op) if slot_of_op is not None else None
+    if len(widths) == 3:  # (master, both moments, compute)
+        widths = (widths[0], widths[1], widths[1], widths[2])
     cfg = _PlanCfg(n_ops, nt, ts, mode, window, n_active, order_a, slots_a, t_iter_s, host_link_Bps, align,
-                   widths[0], widths[1], widths[2])
+                   widths[0], widths[1], widths[2], widths[3])
     out = C.c_void_p()
     _check(_lib.ckpt_plan(C.byref(cfg), C.byref(out)))
     return Plan(out.value)

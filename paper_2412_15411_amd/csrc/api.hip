@@ -416,7 +416,8 @@ int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_acti
                       const moev_state* state, const char* who) {
   if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "%s: null argument", who);
   const auto& h = p->host;
-  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_COMPUTE] != 2)
+  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_ADAM_V] != 4 ||
+      h.width[MOEV_KIND_COMPUTE] != 2)
     return fail(MOEV_E_INVAL, "%s: needs FP32 master and moments and 2-byte compute weights", who);
   if (adam->step == 0) return fail(MOEV_E_INVAL, "%s: step counts from 1", who);
   int rc = check_state(p, state, who);

@@ -69,7 +69,8 @@ int build_plan(const moev_plan_cfg& cfg, HostPlan& p, std::string& err) {
     return MOEV_E_INVAL;
   }
   p.width[MOEV_KIND_MASTER] = cfg.master_bytes ? cfg.master_bytes : 4;
-  p.width[MOEV_KIND_ADAM_M] = p.width[MOEV_KIND_ADAM_V] = cfg.opt_bytes_each ? cfg.opt_bytes_each : 4;
+  p.width[MOEV_KIND_ADAM_M] = cfg.m_bytes ? cfg.m_bytes : 4;
+  p.width[MOEV_KIND_ADAM_V] = cfg.v_bytes ? cfg.v_bytes : 4;
   p.width[MOEV_KIND_COMPUTE] = cfg.compute_bytes ? cfg.compute_bytes : 2;
   for (uint8_t w : p.width)
     if (w != 1 && w != 2 && w != 4 && w != 8) {
@@ -223,6 +224,7 @@ int build_plan(const moev_plan_cfg& cfg, HostPlan& p, std::string& err) {
   f.add<uint32_t>(p.align);
   f.add<uint8_t>(p.width[MOEV_KIND_MASTER]);
   f.add<uint8_t>(p.width[MOEV_KIND_ADAM_M]);
+  f.add<uint8_t>(p.width[MOEV_KIND_ADAM_V]);
   f.add<uint8_t>(p.width[MOEV_KIND_COMPUTE]);
   for (const auto& t : p.tensors) {
     f.add<uint32_t>(t.op);

@@ -56,16 +56,17 @@ class Workload:
             out[op] += n
         return out
 
-    def slot_payload_bytes(self, slot: int, widths=(4, 4, 2)) -> int:
+    def slot_payload_bytes(self, slot: int, widths=(4, 4, 4, 2)) -> int:
         """Unpadded bytes a snapshot of `slot` carries: full state of the operators scheduled
-        in the slot plus compute weights of the operators scheduled later."""
-        full = widths[0] + 2 * widths[1]
+        in the slot plus compute weights of the operators scheduled later.
+        widths = bytes per element of master, Adam m, Adam v, compute."""
+        full = widths[0] + widths[1] + widths[2]
         total = 0
         for e, p in enumerate(self.params_of_op()):
             if self.slot_of_op[e] == slot:
                 total += full * p
             elif self.slot_of_op[e] > slot:
-                total += widths[2] * p
+                total += widths[3] * p
         return total
 
     def active_params_at(self, i: int) -> int:

@@ -5,7 +5,7 @@ import torch
 import oracle
 
 
-def model_of(wl, align=256, widths=(4, 4, 2)):
+def model_of(wl, align=256, widths=(4, 4, 4, 2)):
     return oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, align, widths)
 
 

@@ -36,7 +36,7 @@ int main(void) {
     if (orc_generate_schedule(n_ops, order, a, slots, &window) != ORC_OK) return 1;
     if (orc_check_schedule(n_ops, order, slots, window) != ORC_OK) return 2;
     const uint32_t aligns[] = {16, 64, 256, 1024};
-    orc_model mdl = {n_ops, n_tensors, tensors, order, slots, window, aligns[rnd() % 4], {4, 4, 2}};
+    orc_model mdl = {n_ops, n_tensors, tensors, order, slots, window, aligns[rnd() % 4], {4, 4, 4, 2}};
     void *master[32], *m[32], *v[32], *c[32];
     float* grads[32];
     for (uint32_t t = 0; t < n_tensors; ++t) {

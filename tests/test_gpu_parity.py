@@ -277,6 +277,48 @@ def test_degenerate_slots(orc, dev):
                 assert np.array_equal(mask.cpu().numpy(), ref_mask)
 
 
+@pytest.mark.parametrize("widths", [(2, 2, 2, 2), (4, 4, 4, 1), (2, 1, 2, 1), (1, 1, 2, 1)],
+                         ids=["fp16_state", "fp8_compute", "fp8_m_fp16_v", "fp8_master"])
+def test_low_precision_regimes_pack_unpack(orc, dev, widths):
+    """Sec. 5.6 regimes: pack and unpack are byte copies whatever the element widths are (odd byte
+    counts, 1-byte elements); no compute weights are derived outside the FP32-master regime."""
+    wl = ragged_workload(60 + sum(widths), max_numel=30000)
+    kinds_w = dict(zip(KINDS, widths))
+    g = torch.Generator().manual_seed(7)
+    st_cpu = {k: [torch.randint(0, 256, (n * kinds_w[k],), dtype=torch.uint8, generator=g) for _, n in wl.tensors]
+              for k in KINDS}
+    model = orc.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, 64, widths)
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
+                       align=64, widths=widths)
+    import oracle
+    ref_state = oracle.State(*[[t.numpy().copy() for t in st_cpu[k]] for k in KINDS])
+    ds = DeviceState(st_cpu, dev)
+    buf = packed_buffer(plan, dev)
+    for k in range(wl.window):
+        buf.fill_(0xA5)
+        B.snapshot_pack(plan, k, 4, ds.state, buf)
+        torch.cuda.synchronize()
+        exp = orc.pack(model, k, 4, ref_state)
+        assert buf.cpu().numpy()[:exp.size].tobytes() == exp.tobytes()
+        target = DeviceState(st_cpu, dev)
+        for kind in KINDS:
+            for v in target.views[kind]:
+                v.fill_(0xEE)
+        ref = oracle.State(*[[v.cpu().numpy().copy() for v in target.views[kk]] for kk in KINDS])
+        ref_mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        orc.unpack(model, k, exp, ref, ref_mask)
+        mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+        B.restore_unpack(plan, k, None, buf, target.state, mask)
+        torch.cuda.synchronize()
+        got = oracle.State(*[[v.cpu().numpy().copy() for v in target.views[kk]] for kk in KINDS])
+        assert states_equal(got, ref) == [] and target.guards_intact()
+        assert np.array_equal(mask.cpu().numpy(), ref_mask)
+    mask = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    with pytest.raises(B.MoevError) as e:   # the replay kernel exists for FP32 state + 2-byte compute weights only
+        B.convert_replay(plan, 1e-4, 0.9, 0.95, 1e-8, 0.0, 11, mask, [None] * wl.n_tensors, ds.state)
+    assert e.value.code == B.E_INVAL
+
+
 def test_pack_drain_restore_roundtrip_through_pinned_host(orc, dev):
     """pack -> drain (side stream, event-ordered) -> host bytes equal the oracle's snapshot;
     restore from the pinned copy (H2D + scatter) brings a poisoned state back: identity."""

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(B.EXPORTS)
 
 
-def _plan_of(wl, mode="explicit", align=0, widths=(0, 0, 0), n_active=0):
+def _plan_of(wl, mode="explicit", align=0, widths=(0, 0, 0, 0), n_active=0):
     if mode == "explicit":
         return B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, align=align,
                            widths=widths)
@@ -72,6 +72,34 @@ def test_plan_matches_oracle(orc, wl, align):
         assert B.ckpt_plan_active_params(plan, k) == wl.active_params_at(k)
     assert B.ckpt_plan_max_packed_bytes(plan) == biggest
     assert B.ckpt_plan_packed_bytes(plan, wl.window) == 0
+
+
+# (compute, master, optimizer) regimes of Sec. 5.6 as element widths (master, m, v, compute)
+REGIMES = {
+    "fp16/fp32/fp32+fp32 (default)": (4, 4, 4, 2),
+    "fp16/fp16/fp16+fp16": (2, 2, 2, 2),
+    "fp8/fp32/fp32+fp32": (4, 4, 4, 1),
+    "fp8/fp16/fp32+fp32": (2, 4, 4, 1),
+    "fp8/fp16/fp8+fp16": (2, 1, 2, 1),
+    "fp8/fp8/fp8+fp16": (1, 1, 2, 1),
+}
+
+
+@pytest.mark.parametrize("widths", list(REGIMES.values()), ids=list(REGIMES))
+def test_low_precision_layouts_match_oracle(orc, widths):
+    """Sec. 5.6: other precisions of compute weights, master weights and optimizer state only change
+    the element widths of the snapshot layout."""
+    wl = W.fine_grained_stack(n_layers=1, n_routed=8, n_shared=2, d_model=24, d_ff=13, per_slot=2)
+    plan, model = _plan_of(wl, widths=widths), model_of(wl, widths=widths)
+    assert B.ckpt_plan_hash(plan) == orc.plan_hash(model)
+    full = widths[0] + widths[1] + widths[2]
+    for k in range(wl.window):
+        segs, total = orc.layout(model, k)
+        assert B.ckpt_plan_segments(plan, k) == segs and B.ckpt_plan_packed_bytes(plan, k) == total
+        assert sum(s[2] for s in segs) == wl.slot_payload_bytes(k, widths=widths)
+    # "reduces the snapshot size by as much as 66%": FP8 master + FP8/FP16 moments against FP32 everywhere
+    if widths == (1, 1, 2, 1):
+        assert round(100 * (1 - full / 12)) in (66, 67)
 
 
 def test_fixed_mode_matches_generate_schedule(orc):
@@ -128,7 +156,7 @@ def test_plan_rejects_bad_configurations():
         dict(tensors=t, mode=B.AUTO, t_iter_s=1.0, host_link_Bps=0.0),
         dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], align=48),          # not a power of two
         dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], align=8),
-        dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], widths=(3, 4, 2)),
+        dict(tensors=t, mode=B.EXPLICIT, window=1, slot_of_op=[0, 0, 0], widths=(3, 4, 4, 2)),
         dict(tensors=t, mode=7),
     ]
     for kw in bad:

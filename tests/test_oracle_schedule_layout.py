@@ -267,7 +267,8 @@ def test_plan_hash_distinguishes(orc):
     other.tensors[0] = (other.tensors[0][0], other.tensors[0][1] + 1)
     assert orc.plan_hash(model_of(other)) != base
     assert orc.plan_hash(model_of(wl, align=512)) != base
-    assert orc.plan_hash(model_of(wl, widths=(4, 4, 1))) != base
+    assert orc.plan_hash(model_of(wl, widths=(4, 4, 4, 1))) != base
+    assert orc.plan_hash(model_of(wl, widths=(4, 4, 2, 2))) != base
     assert orc.plan_hash(model_of(wl)) == base
 
 
