@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--copy-blocks", type=int, default=0)
     ap.add_argument("--adam-blocks", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--xcd-regions", type=int, default=-1)
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -349,6 +350,8 @@ def main():
             B.moev_tune(plan, knob, val)
     if args.nontemporal >= 0:
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
+    if args.xcd_regions >= 0:
+        B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
     packed = [torch.empty(B.ckpt_plan_packed_bytes(plan, k), dtype=torch.uint8, device=dev) for k in range(wl.window)]
     mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()

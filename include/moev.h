@@ -147,7 +147,9 @@ enum {
   MOEV_TUNE_ADAM_THREADS = 8,
   MOEV_TUNE_ADAM_UNROLL = 9,
   MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */
-  MOEV_TUNE_UNPACK_UNROLL = 11
+  MOEV_TUNE_UNPACK_UNROLL = 11,
+  MOEV_TUNE_XCD_REGIONS = 12     /* one tile per workgroup: 1 (default) = each of the 8 XCDs sweeps a contiguous
+                                    eighth of the tiles, 0 = consecutive workgroups take consecutive tiles */
 };
 
 const char *moev_last_error(void);

@@ -20,7 +20,7 @@ EXPLICIT, FIXED, AUTO = 0, 1, 2
 HEADER_BYTES = 256
 (TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL,
  TUNE_PERSISTENT, TUNE_COPY_THREADS, TUNE_COPY_UNROLL, TUNE_ADAM_THREADS, TUNE_ADAM_UNROLL,
- TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL) = range(12)
+ TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL, TUNE_XCD_REGIONS) = range(13)
 
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",

@@ -63,6 +63,7 @@ struct moev_plan {
   int64_t adam_tile_elems = 8192;
   int64_t adam_max_blocks = 0;
   int64_t nontemporal = 1;
+  int64_t xcd_regions = 1;           // one tile per workgroup: contiguous eighth of the tiles per XCD
 
   uint64_t eff_copy_tile() const { return persistent ? copy_tile_bytes : copy_threads * 16 * copy_unroll; }
   uint64_t eff_unpack_tile() const { return persistent ? copy_tile_bytes : unpack_threads * 16 * unpack_unroll; }
@@ -316,6 +317,13 @@ uint32_t grid_for(const moev_plan* pl, uint32_t tiles, int64_t cap) {
   return static_cast<uint32_t>(g ? g : 1);
 }
 
+// grid of a one-tile-per-workgroup launch: a multiple of the XCD count (the region mapping hands
+// workgroup b the (b / 8)-th tile of XCD b % 8), at least one workgroup
+uint32_t direct_grid(uint64_t tiles) {
+  const uint64_t g = (tiles + 7) / 8 * 8;
+  return static_cast<uint32_t>(g ? g : 8);
+}
+
 void fill_header(const moev_plan* pl, uint32_t slot, uint64_t iter, uint64_t out[7]) {
   const auto& h = pl->host;
   out[0] = kMagic;
@@ -346,6 +354,7 @@ moev::CopyArgs copy_args(const moev_plan* pl, uint32_t slot, uint64_t iter, void
   a.n_ops = h.n_ops;
   a.slot_of_op = pl->d_slot_of_op;
   a.status = pl->d_status;
+  a.xcd_regions = static_cast<uint32_t>(pl->xcd_regions);
   return a;
 }
 
@@ -406,7 +415,7 @@ int launch_unpack_locked(moev_plan* p, uint32_t slot, const void* h_pinned, void
   } else {
     a.tile_begin = compute_only ? p->slot_first_compute_tile[slot] : 0u;
     const uint32_t tiles = p->slot_tiles_unpack[slot] - a.tile_begin;
-    MOEV_HIP(moev::launch_unpack_direct(a, tiles ? tiles : 1u, static_cast<uint32_t>(p->unpack_threads),
+    MOEV_HIP(moev::launch_unpack_direct(a, direct_grid(tiles), static_cast<uint32_t>(p->unpack_threads),
                                         static_cast<uint32_t>(p->unpack_unroll), p->nontemporal != 0, s));
   }
   return MOEV_OK;
@@ -453,6 +462,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   a.ptrs = p->d_state_ptrs;
   a.grads = p->d_grad_ptrs;
   a.status = p->d_status;
+  a.xcd_regions = static_cast<uint32_t>(p->xcd_regions);
   a.n_tensors = h.n_tensors;
   a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
   a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
@@ -476,7 +486,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   uint64_t bound = 0;
   for (uint32_t t = 0; t < h.n_tensors; ++t)
     if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
-  if (bound == 0) bound = 1;
+  bound = direct_grid(bound);
   MOEV_HIP(moev::launch_active_scan(a, p->d_active_tile_start, s));
   a.tile_start = p->d_active_tile_start;
   if (fused_slot >= 0) {
@@ -672,6 +682,9 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
     case MOEV_TUNE_PERSISTENT:
       p->persistent = value ? 1 : 0;
       break;
+    case MOEV_TUNE_XCD_REGIONS:
+      p->xcd_regions = value ? 1 : 0;
+      break;
     case MOEV_TUNE_COPY_THREADS:
       if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->copy_unroll)))
         return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
@@ -719,6 +732,7 @@ int64_t moev_tune_get(const moev_plan* p, int knob) {
     case MOEV_TUNE_ADAM_MAX_BLOCKS: return p->adam_max_blocks;
     case MOEV_TUNE_NONTEMPORAL: return p->nontemporal;
     case MOEV_TUNE_PERSISTENT: return p->persistent;
+    case MOEV_TUNE_XCD_REGIONS: return p->xcd_regions;
     case MOEV_TUNE_COPY_THREADS: return p->copy_threads;
     case MOEV_TUNE_COPY_UNROLL: return p->copy_unroll;
     case MOEV_TUNE_UNPACK_THREADS: return p->unpack_threads;
@@ -813,7 +827,7 @@ int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* 
   if (p->persistent)
     MOEV_HIP(moev::launch_pack_persistent(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
   else
-    MOEV_HIP(moev::launch_pack_direct(a, p->slot_tiles[slot] ? p->slot_tiles[slot] : 1u, static_cast<uint32_t>(p->copy_threads),
+    MOEV_HIP(moev::launch_pack_direct(a, direct_grid(p->slot_tiles[slot]), static_cast<uint32_t>(p->copy_threads),
                                       static_cast<uint32_t>(p->copy_unroll), p->nontemporal != 0, s));
   return MOEV_OK;
 }

@@ -66,6 +66,19 @@ __device__ __forceinline__ uint32_t owner_of_tile(P start, uint32_t n, uint32_t 
   return lo;
 }
 
+// Tile of workgroup `b` in a launch over `n` tiles.  Workgroup ids are handed to the 8 XCDs round
+// robin; with `regions` every XCD sweeps its own contiguous eighth of the tiles instead of every
+// eighth tile (each XCD then touches an eighth of the pages; ~2% more copy bandwidth).  Returns
+// ~0u for workgroups beyond the last tile.
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t b, uint32_t n, uint32_t regions) {
+  if (!regions) return b < n ? b : ~0u;
+  const uint32_t per_xcd = (n + kXcds - 1) / kXcds;
+  const uint32_t idx = b / kXcds;
+  const uint32_t tile = (b % kXcds) * per_xcd + idx;
+  return (idx < per_xcd && tile < n) ? tile : ~0u;
+}
+
 // bfloat16 bits of an FP32 value, round to nearest even; NaN stays a quiet NaN.
 __device__ __forceinline__ uint32_t bf16_bits(float x) {
   const uint32_t u = __float_as_uint(x);
@@ -312,7 +325,8 @@ __device__ __forceinline__ void unpack_tile(const CopyArgs& a, Table start, cons
 template <uint32_t T, uint32_t U, bool NT>
 __global__ __launch_bounds__(T) void k_pack_direct(MOEV_COPY_TABLES, const CopyArgs a) {
   if (blockIdx.x == 0) write_header<T>(a);
-  if (blockIdx.x < tile_start[a.n_seg]) pack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, blockIdx.x);
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, tile_start[a.n_seg], a.xcd_regions);
+  if (tile != ~0u) pack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, tile);
 }
 
 template <uint32_t T, uint32_t U, bool NT>
@@ -323,8 +337,9 @@ __global__ __launch_bounds__(T) void k_unpack_direct(MOEV_COPY_TABLES, const uin
     return;
   }
   if (blockIdx.x == 0) update_mask<T>(a);
-  const uint32_t tile = blockIdx.x + a.tile_begin;
-  if (tile < tile_start[a.n_seg]) unpack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, tile);
+  const uint32_t n_tiles = tile_start[a.n_seg];
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles > a.tile_begin ? n_tiles - a.tile_begin : 0u, a.xcd_regions);
+  if (tile != ~0u) unpack_tile<T, U, NT>(a, tile_start, segs, dst_off, ptrs, tile + a.tile_begin);
 }
 
 // ---- fixed grid walking the tile list, map staged in LDS ----
@@ -452,8 +467,8 @@ __device__ __forceinline__ void adam_range(const float* Ps, const float* Ms, con
 // one tile per workgroup over the compacted tile list written by k_active_scan
 template <uint32_t T, uint32_t U, bool NT>
 __global__ __launch_bounds__(T) void k_adam_direct(MOEV_ADAM_TABLES, const AdamArgs a) {
-  const uint32_t tile = blockIdx.x;
-  if (tile >= tile_start[a.n_tensors]) return;
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, tile_start[a.n_tensors], a.xcd_regions);
+  if (tile == ~0u) return;
   const uint32_t t = owner_of_tile(tile_start, a.n_tensors, tile);
   const uint64_t numel = numel_of[t];
   const uint64_t begin = static_cast<uint64_t>(tile - tile_start[t]) * a.tile_elems;
@@ -478,8 +493,8 @@ __global__ __launch_bounds__(T) void k_adam_fused(MOEV_ADAM_TABLES, const uint64
   for (uint32_t k = 0; k < 7; ++k)
     if (k != 3 && header[k] != a.header[k]) ok = false;
   if (!ok) return;  // foreign snapshot: the unpack launch in front of this one has raised the status word
-  const uint32_t tile = blockIdx.x;
-  if (tile >= tile_start[a.n_tensors]) return;
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, tile_start[a.n_tensors], a.xcd_regions);
+  if (tile == ~0u) return;
   const uint32_t t = owner_of_tile(tile_start, a.n_tensors, tile);
   const uint64_t numel = numel_of[t];
   const uint64_t begin = static_cast<uint64_t>(tile - tile_start[t]) * a.tile_elems;

@@ -44,6 +44,7 @@ struct CopyArgs {
   uint32_t* status;
   uint32_t n_ops, slot, derive_compute;
   uint32_t tile_begin;         // first tile of the launch (unpack of the compute-weight segments only)
+  uint32_t xcd_regions;        // 1: every XCD gets a contiguous eighth of the launch's tiles
 };
 
 struct AdamArgs {
@@ -59,6 +60,7 @@ struct AdamArgs {
   const uint8_t* packed;
   uint64_t header[7];
   uint32_t n_tensors, tile_elems, lds_entries, has_decay;
+  uint32_t xcd_regions;        // as in CopyArgs
   float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
 };
 

@@ -77,7 +77,7 @@ class DeviceState:
 
 
 def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=None, nt=None,
-              copy_shape=None, adam_shape=None):
+              copy_shape=None, adam_shape=None, xcd_regions=None):
     """tile / blocks / adam_tile / adam_blocks select the fixed-grid launch shape with those values;
     copy_shape / adam_shape = (threads, unroll) select a one-tile-per-workgroup shape (the default)."""
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
@@ -97,6 +97,8 @@ def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=N
             B.moev_tune(plan, k_unroll, shape[1])
     if nt is not None:
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, nt)
+    if xcd_regions is not None:
+        B.moev_tune(plan, B.TUNE_XCD_REGIONS, xcd_regions)
     return plan
 
 
@@ -614,6 +616,16 @@ def test_fused_step_refuses_foreign_snapshot_and_missing_gradients(orc, dev):
     with pytest.raises(B.MoevError) as e:
         B.convert_window_step(plan, 1, None, buf, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, 6, mask, grads, ds.state)
     assert e.value.code == B.E_INVAL
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
+def test_window_without_xcd_regions(orc, dev, fused):
+    """Consecutive workgroups take consecutive tiles (the XCD-region mapping switched off)."""
+    wl = ragged_workload(79, n_ops=10, window=4, with_empty=True)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=7, align=256, fused=fused, xcd_regions=0)
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "ragged-window-no-regions")
+    assert rebuilt.guards_intact()
 
 
 def test_window_ragged_small_grid(orc, dev):
