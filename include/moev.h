@@ -286,6 +286,40 @@ int convert_window_step(moev_plan *plan, uint32_t slot, const void *h_pinned, vo
                         const moev_adam *adam, uint8_t *d_active_mask, void *const *grads,
                         const moev_state *state, void *stream);
 
+/* ---- upstream logging ring (Sec. 3.4) ---------------------------------------------------
+ * Stage-boundary tensors (kind 0: activations passed downstream in the forward pass, kind 1:
+ * gradients passed upstream in the backward pass) are copied to pinned host memory at the
+ * sender, tagged (iteration, micro-batch), kept until the sparse checkpoint that supersedes
+ * them has persisted, and copied back to the GPU when a neighbouring stage recovers locally.
+ * The ring lives in ONE caller-owned pinned buffer; entries are laid out in arrival order and
+ * never wrap (a tail too short for the next entry is skipped); iterations must not go backwards.
+ *
+ * uplog_create   ring over h_pinned_ring[ring_bytes] (16-byte aligned), at most max_entries live entries.
+ * uplog_reserve  host bookkeeping only: claims room for an entry and returns its offset
+ *                (MOEV_E_NOMEM when the ring is full: run uplog_gc, or the training loop must stall;
+ *                MOEV_E_INVAL for a duplicate tag or a kind other than 0 / 1).
+ * uplog_append   uplog_reserve + one async device-to-host copy on side_stream, after `ready`
+ *                (an event recorded when the tensor is complete; may be NULL).
+ * uplog_find     host pointer and size of a logged tensor (valid after the side stream has been
+ *                synchronised), MOEV_E_RANGE if it is not (or no longer) in the ring.
+ * uplog_replay   async host-to-device copy of a logged tensor into d_dst[cap] on `stream`.
+ * uplog_gc       "stale log cleanup": drops every entry with iteration < first_kept_iter; returns
+ *                the number of entries dropped.
+ */
+typedef struct moev_uplog moev_uplog;
+int uplog_create(void *h_pinned_ring, size_t ring_bytes, uint32_t max_entries, moev_uplog **out);
+void uplog_free(moev_uplog *log);
+int uplog_reserve(moev_uplog *log, uint64_t iter, uint32_t micro_batch, uint32_t kind, size_t nbytes,
+                  uint64_t *offset_out);
+int uplog_append(moev_uplog *log, uint64_t iter, uint32_t micro_batch, uint32_t kind, const void *d_tensor,
+                 size_t nbytes, void *side_stream, void *ready);
+int uplog_find(moev_uplog *log, uint64_t iter, uint32_t micro_batch, uint32_t kind, const void **h_ptr,
+               size_t *nbytes);
+int uplog_replay(moev_uplog *log, uint64_t iter, uint32_t micro_batch, uint32_t kind, void *d_dst, size_t cap,
+                 void *stream);
+int64_t uplog_gc(moev_uplog *log, uint64_t first_kept_iter);
+int uplog_stats(moev_uplog *log, uint64_t *entries, uint64_t *bytes_in_use, uint64_t *capacity);
+
 /* ---- measurement hook --------------------------------------------------------------------
  * moev_copy_probe: plain contiguous device-to-device copy of nbytes (multiple of 16, both
  * pointers 16-byte aligned) with the same access shape as the gather kernel.  It is the

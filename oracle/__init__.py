@@ -375,3 +375,28 @@ def convert(model: Model, snaps: List[np.ndarray], hp: AdamHP, grads_of_step, st
         if trace is not None:
             trace.append(("replay", it + 1, mask.copy()))
     return mask
+
+
+# --------------------------------------------------------------------------------------
+# upstream logging (Sec. 3.4)
+# --------------------------------------------------------------------------------------
+class UpstreamLog:
+    """What upstream logging keeps (Sec. 3.4): stage-boundary tensors, activations of the forward
+    pass (kind 0) and gradients of the backward pass (kind 1), tagged with the iteration and the
+    micro-batch; logs older than the latest persisted sparse checkpoint are dropped."""
+
+    def __init__(self):
+        self.store = {}
+
+    def append(self, it: int, micro_batch: int, kind: int, data: bytes) -> None:
+        assert kind in (0, 1) and (it, micro_batch, kind) not in self.store
+        self.store[(it, micro_batch, kind)] = bytes(data)
+
+    def find(self, it: int, micro_batch: int, kind: int):
+        return self.store.get((it, micro_batch, kind))
+
+    def gc(self, first_kept_iter: int) -> int:
+        stale = [k for k in self.store if k[0] < first_kept_iter]
+        for k in stale:
+            del self.store[k]
+        return len(stale)

@@ -30,7 +30,8 @@ EXPORTS = [
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
     "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
-    "moev_copy_probe",
+    "moev_copy_probe", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
+    "uplog_gc", "uplog_stats",
 ]
 
 
@@ -122,6 +123,16 @@ def _load():
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.convert_window_step.argtypes = [vp, u32, vp, vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
+    lib.uplog_create.argtypes = [vp, C.c_size_t, u32, C.POINTER(vp)]
+    lib.uplog_free.argtypes = [vp]
+    lib.uplog_free.restype = None
+    lib.uplog_reserve.argtypes = [vp, u64, u32, u32, C.c_size_t, C.POINTER(u64)]
+    lib.uplog_append.argtypes = [vp, u64, u32, u32, vp, C.c_size_t, vp, vp]
+    lib.uplog_find.argtypes = [vp, u64, u32, u32, C.POINTER(vp), C.POINTER(C.c_size_t)]
+    lib.uplog_replay.argtypes = [vp, u64, u32, u32, vp, C.c_size_t, vp]
+    lib.uplog_gc.argtypes = [vp, u64]
+    lib.uplog_gc.restype = i64
+    lib.uplog_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
     return lib
 
 
@@ -358,3 +369,66 @@ def convert_window_step(plan, slot: int, h_pinned, d_packed, lr, beta1, beta2, e
 
 def moev_copy_probe(d_dst, d_src, nbytes: int, blocks: int = 0, nontemporal: int = 1, stream=None):
     _check(_lib.moev_copy_probe(_addr(d_dst), _addr(d_src), nbytes, blocks, nontemporal, _stream(stream)))
+
+
+# ---- upstream logging ring -----------------------------------------------------------------
+ACTIVATION, GRADIENT = 0, 1
+
+
+class UpLog:
+    """Owner of a moev_uplog* over a caller-owned pinned host buffer (kept alive here)."""
+
+    def __init__(self, handle: int, ring):
+        self.handle = C.c_void_p(handle)
+        self.ring = ring
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.uplog_free(h)
+
+
+def uplog_create(h_pinned_ring, ring_bytes: Optional[int] = None, max_entries: int = 4096) -> UpLog:
+    if ring_bytes is None:
+        ring_bytes = h_pinned_ring.numel() * h_pinned_ring.element_size()
+    out = C.c_void_p()
+    _check(_lib.uplog_create(_addr(h_pinned_ring), ring_bytes, max_entries, C.byref(out)))
+    return UpLog(out.value, h_pinned_ring)
+
+
+def uplog_reserve(log: UpLog, it: int, micro_batch: int, kind: int, nbytes: int) -> int:
+    off = C.c_uint64()
+    _check(_lib.uplog_reserve(log.handle, it, micro_batch, kind, nbytes, C.byref(off)))
+    return off.value
+
+
+def uplog_append(log: UpLog, it: int, micro_batch: int, kind: int, d_tensor, nbytes: Optional[int] = None,
+                 side_stream=None, ready=None) -> None:
+    if nbytes is None:
+        nbytes = d_tensor.numel() * d_tensor.element_size()
+    _check(_lib.uplog_append(log.handle, it, micro_batch, kind, _addr(d_tensor), nbytes, _stream(side_stream),
+                             _event(ready)))
+
+
+def uplog_find(log: UpLog, it: int, micro_batch: int, kind: int):
+    """-> (host address, nbytes)."""
+    p, n = C.c_void_p(), C.c_size_t()
+    _check(_lib.uplog_find(log.handle, it, micro_batch, kind, C.byref(p), C.byref(n)))
+    return p.value, n.value
+
+
+def uplog_replay(log: UpLog, it: int, micro_batch: int, kind: int, d_dst, cap: Optional[int] = None, stream=None):
+    if cap is None:
+        cap = d_dst.numel() * d_dst.element_size()
+    _check(_lib.uplog_replay(log.handle, it, micro_batch, kind, _addr(d_dst), cap, _stream(stream)))
+
+
+def uplog_gc(log: UpLog, first_kept_iter: int) -> int:
+    return _check(_lib.uplog_gc(log.handle, first_kept_iter))
+
+
+def uplog_stats(log: UpLog):
+    """-> (live entries, bytes in use, capacity)."""
+    e, b, c = C.c_uint64(), C.c_uint64(), C.c_uint64()
+    _check(_lib.uplog_stats(log.handle, C.byref(e), C.byref(b), C.byref(c)))
+    return e.value, b.value, c.value

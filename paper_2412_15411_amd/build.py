@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoev.so")
-SOURCES = ["plan.cpp", "kernels.hip", "api.hip"]
+SOURCES = ["plan.cpp", "kernels.hip", "api.hip", "uplog.hip"]
 
 # -ffp-contract=off: the Adam replay's operation order is part of its contract (no FMA).
 # Correctly rounded FP32 divide / sqrt and denormal support are stated explicitly.

@@ -31,6 +31,23 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
+}  // namespace
+
+namespace moev {
+// for the library's other translation units: records the message behind moev_last_error()
+int set_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+}  // namespace moev
+
+namespace {
+
 #define MOEV_HIP(call)                                                                     \
   do {                                                                                     \
     hipError_t e_ = (call);                                                                \
