@@ -53,7 +53,7 @@ def parse_args():
 
 
 # ---------------------------------------------------------------------------------------
-# algorithmic bytes (what the method itself must move; stated per unit in the design doc)
+# algorithmic bytes: what the method itself must move per slot and per replayed iteration
 # ---------------------------------------------------------------------------------------
 def pack_bytes(wl, k):
     return 2 * wl.slot_payload_bytes(k)            # read every payload byte once, write it once
