@@ -143,7 +143,7 @@ enum {
   MOEV_TUNE_NONTEMPORAL = 4,     /* 1 = streaming (nontemporal) loads and stores, 0 = default caching */
   MOEV_TUNE_PERSISTENT = 5,      /* 0 = one tile per workgroup, 1 = fixed grid */
   MOEV_TUNE_COPY_THREADS = 6,    /* one tile per workgroup: threads (64..1024) and accesses per lane (1, 2, 4); */
-  MOEV_TUNE_COPY_UNROLL = 7,     /*   supported pairs: (64|128|256|512|1024, 1), (256|512, 2), (256, 4) */
+  MOEV_TUNE_COPY_UNROLL = 7,     /*   supported pairs: (64|128|256|512|1024, 1), (64|128|256|512, 2), (64|128|256, 4) */
   MOEV_TUNE_ADAM_THREADS = 8,
   MOEV_TUNE_ADAM_UNROLL = 9,
   MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */

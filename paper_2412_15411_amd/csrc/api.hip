@@ -73,7 +73,7 @@ struct moev_plan {
   // launch knobs
   int64_t persistent = 0;            // 0: one tile per workgroup, 1: fixed grid walking the tile list
   int64_t copy_threads = 256, copy_unroll = 1;   // one-tile-per-workgroup shape of the pack
-  int64_t unpack_threads = 256, unpack_unroll = 2;  // ... of the unpack
+  int64_t unpack_threads = 128, unpack_unroll = 2;  // ... of the unpack
   int64_t adam_threads = 64, adam_unroll = 1;
   int64_t copy_tile_bytes = 32768;   // fixed-grid shape
   int64_t copy_max_blocks = 0;

@@ -595,7 +595,11 @@ namespace {
 
 #define MOEV_DIRECT_ALL(KERNEL)     \
   MOEV_DIRECT_CASE(KERNEL, 64, 1)   \
+  MOEV_DIRECT_CASE(KERNEL, 64, 2)   \
+  MOEV_DIRECT_CASE(KERNEL, 64, 4)   \
   MOEV_DIRECT_CASE(KERNEL, 128, 1)  \
+  MOEV_DIRECT_CASE(KERNEL, 128, 2)  \
+  MOEV_DIRECT_CASE(KERNEL, 128, 4)  \
   MOEV_DIRECT_CASE(KERNEL, 256, 1)  \
   MOEV_DIRECT_CASE(KERNEL, 256, 2)  \
   MOEV_DIRECT_CASE(KERNEL, 256, 4)  \
@@ -608,7 +612,8 @@ namespace {
 
 bool direct_shape_supported(uint32_t threads, uint32_t unroll) {
   return (unroll == 1 && (threads == 64 || threads == 128 || threads == 256 || threads == 512 || threads == 1024)) ||
-         (unroll == 2 && (threads == 256 || threads == 512)) || (unroll == 4 && threads == 256);
+         (unroll == 2 && (threads == 64 || threads == 128 || threads == 256 || threads == 512)) ||
+         (unroll == 4 && (threads == 64 || threads == 128 || threads == 256));
 }
 
 #define MOEV_LAUNCH_ARGS a.tile_start, a.segs, a.dst_off, a.ptrs, a

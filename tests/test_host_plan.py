@@ -173,7 +173,7 @@ def test_tune_knobs_validate():
     B.moev_tune(plan, B.TUNE_COPY_THREADS, 512)
     B.moev_tune(plan, B.TUNE_COPY_UNROLL, 2)
     for knob, value in [(B.TUNE_COPY_TILE_BYTES, 1000), (B.TUNE_ADAM_TILE_ELEMS, 100), (B.TUNE_COPY_MAX_BLOCKS, -1), (99, 1),
-                        (B.TUNE_COPY_UNROLL, 4), (B.TUNE_COPY_THREADS, 100), (B.TUNE_ADAM_UNROLL, 3)]:
+                        (B.TUNE_COPY_UNROLL, 4), (B.TUNE_COPY_THREADS, 100), (B.TUNE_ADAM_UNROLL, 3), (B.TUNE_COPY_UNROLL, 8)]:
         with pytest.raises(B.MoevError):
             B.moev_tune(plan, knob, value)
 
