@@ -633,3 +633,69 @@ def test_window_ragged_small_grid(orc, dev):
     rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=5, align=16, tile=4096, blocks=2, adam_tile=1024, adam_blocks=2)
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "ragged-window")
+
+
+def test_recovery_from_a_failure_mid_run(orc, dev):
+    """Sec. 3.6 end to end on the GPU: snapshots every iteration (slot (t - t0) mod W) packed and
+    drained to pinned host memory while the run goes on; at a failure the live state is discarded,
+    the last complete window is converted from the host copies (fused load + replay), the remaining
+    iterations are re-executed, and the result equals the uninterrupted run bit for bit (and the
+    oracle's uninterrupted run within 1e-6)."""
+    wl = ragged_workload(91, n_ops=8, window=3, max_numel=40000, with_empty=False)
+    model, hp = model_of(wl), hp_of(wl)
+    w, t0 = wl.window, wl.t0
+    last = t0 + 3 * w + 1
+    st_cpu = W.make_state(wl, seed=11)
+    grads_cpu = {t: W.make_grads(wl, t, seed=11) for t in range(t0 + 1, last + 1)}
+    grads_dev = {t: [g.to(dev) for g in gs] for t, gs in grads_cpu.items()}
+    # oracle: uninterrupted run
+    ref = state_of(st_cpu)
+    ref_states = {}
+    everyone_np = np.ones(wl.n_ops, dtype=np.uint8)
+    for t in range(t0, last):
+        orc.replay_step(model, hp, t + 1, everyone_np, [np_of(g) for g in grads_cpu[t + 1]], ref)
+        ref_states[t + 1] = ref.clone()
+    # GPU: uninterrupted run with a snapshot + drain per iteration
+    plan = make_plan(wl)
+    live = DeviceState(st_cpu, dev)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    everyone = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    cap = B.ckpt_plan_max_packed_bytes(plan)
+    d_buf = [torch.empty(cap, dtype=torch.uint8, device=dev) for _ in range(2)]   # double buffer
+    buf_free = [torch.cuda.Event(), torch.cuda.Event()]
+    host, gpu_states = {}, {}
+    for t in range(t0, last):
+        b = (t - t0) % 2
+        host[t] = torch.empty(cap, dtype=torch.uint8).pin_memory()
+        if t - t0 >= 2:
+            main.wait_event(buf_free[b])     # the drain of two iterations ago has released the buffer
+        packed_done = torch.cuda.Event()
+        B.snapshot_pack(plan, (t - t0) % w, t, live.state, d_buf[b], stream=main)
+        packed_done.record(main)
+        B.snapshot_drain(plan, (t - t0) % w, d_buf[b], host[t], side_stream=side, pack_done=packed_done)
+        buf_free[b].record(side)
+        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, t + 1, everyone, grads_dev[t + 1],
+                         live.state, stream=main)
+        main.synchronize()
+        gpu_states[t + 1] = live.to_oracle()
+    side.synchronize()
+    for fail_at in (t0 + w, t0 + 2 * w - 1, t0 + 2 * w + 1, last):
+        s = t0 + ((fail_at - t0) // w - 1) * w
+        rebuilt = DeviceState(st_cpu, dev)
+        rebuilt.poison()
+        mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+        scratch = torch.empty(cap, dtype=torch.uint8, device=dev)
+        for i in range(w):
+            assert B.snapshot_peek(plan, i, host[s + i])["iter"] == s + i
+            g = [x if wl.slot_of_op[wl.tensors[k][0]] <= i else None for k, x in enumerate(grads_dev[s + i + 1])]
+            B.convert_window_step(plan, i, host[s + i], scratch, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay,
+                                  s + i + 1, mask, g, rebuilt.state, stream=main)
+            main.synchronize()
+        for t in range(s + w, fail_at):
+            B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, t + 1, everyone,
+                             grads_dev[t + 1], rebuilt.state, stream=main)
+        main.synchronize()
+        B.ckpt_plan_device_status(plan)
+        assert states_equal(rebuilt.to_oracle(), gpu_states[fail_at]) == [], f"failure at {fail_at}"
+        _compare_adam(rebuilt, ref_states[fail_at], f"recovery at {fail_at}")
+        assert rebuilt.guards_intact()

@@ -63,11 +63,16 @@ def test_bf16_rne_all_high_halves_against_definition(orc):
 
 
 def test_bf16_rne_matches_library_cast(orc):
-    """Black-box cross-check against torch's float32 -> bfloat16 conversion on random bit patterns
-    (finite values; NaN payloads are implementation-defined)."""
+    """Black-box cross-check against torch's float32 -> bfloat16 conversion: EVERY 16-bit high half
+    with the low halves {0, 1, 0x7fff, 0x8000, 0x8001, 0xffff}, plus random bit patterns (finite
+    values; NaN payloads are implementation-defined)."""
     g = torch.Generator().manual_seed(3)
     bits = torch.randint(-(1 << 31), (1 << 31) - 1, (20000,), dtype=torch.int32, generator=g)
-    x = bits.view(torch.float32)
+    hi = torch.arange(0, 1 << 16, dtype=torch.int64).repeat_interleave(6)
+    lo = torch.tensor([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=torch.int64).repeat(1 << 16)
+    grid = ((hi << 16) | lo)
+    grid = torch.where(grid >= (1 << 31), grid - (1 << 32), grid).to(torch.int32)
+    x = torch.cat([bits, grid]).view(torch.float32)
     x = x[torch.isfinite(x)]
     lib = x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     got = orc.bf16_rne_array(x.numpy())
@@ -342,3 +347,40 @@ def test_dense_special_case_w1(orc):
     wl = W.Workload("dense", [(0, 50), (1, 33)], [0, 0], 1)
     dense, rebuilt, mask, _, snaps = _run_window(orc, wl, seed=5, align=16)
     assert len(snaps) == 1 and states_equal(dense, rebuilt) == []
+
+
+def test_recovery_from_a_failure_mid_run(orc):
+    """Sec. 3.6: recovery = (1) replay W iterations to rebuild a dense checkpoint from the most recent
+    COMPLETE sparse window, (2) re-execute the iterations after it up to the failure.  Snapshots are
+    taken every iteration, slot (t - t0) mod W; the state after recovery equals the uninterrupted run
+    at the failure iteration, whatever that iteration is, and at most 2W iterations are recomputed."""
+    wl = W.tiny_moe(d_in=8, d_hidden=16)
+    model, hp = model_of(wl), hp_of(wl)
+    w, t0, last = wl.window, wl.t0, wl.t0 + 3 * wl.window + 2
+    grads = _grads_fn(wl, 9)
+    everyone = np.ones(wl.n_ops, dtype=np.uint8)
+    # uninterrupted run, remembering the state after every iteration and every snapshot
+    live = state_of(W.make_state(wl, seed=9))
+    states, snaps = {t0: live.clone()}, {}
+    for t in range(t0, last):
+        snaps[t] = orc.pack(model, (t - t0) % w, t, live)          # SS_t: state after step t, taken during iteration t+1
+        orc.replay_step(model, hp, t + 1, everyone, grads(t + 1), live)
+        states[t + 1] = live.clone()
+    for fail_at in range(t0 + w, last + 1):                          # failure while iteration fail_at + 1 would run
+        # last complete window [s, s+w) with every snapshot taken before the failure: SS_{s+w-1} needs state s+w-1 <= fail_at - 1
+        s = t0 + ((fail_at - t0) // w - 1) * w
+        assert s >= t0 and s + w <= fail_at
+        rebuilt = orc.poisoned_like(live)
+        mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        recomputed = 0
+        for i in range(w):
+            it = orc.unpack(model, i, snaps[s + i], rebuilt, mask)
+            assert it == s + i
+            orc.replay_step(model, hp, it + 1, mask, grads(it + 1), rebuilt)
+            recomputed += 1
+        assert mask.all() and states_equal(rebuilt, states[s + w]) == []
+        for t in range(s + w, fail_at):
+            orc.replay_step(model, hp, t + 1, everyone, grads(t + 1), rebuilt)
+            recomputed += 1
+        assert states_equal(rebuilt, states[fail_at]) == []
+        assert recomputed <= 2 * w
