@@ -111,6 +111,7 @@ struct moev_plan {
   bool state_valid = false, grad_valid = false;
   StageSlot ring[kRing];
   int ring_next = 0;
+  hipEvent_t tables_uploaded = nullptr;     // recorded after the copy out of pinned_tables
   std::vector<uint32_t> slot_tiles, slot_tiles_unpack;  // host-side tile counts (grid sizing only)
   std::vector<uint32_t> slot_first_compute_tile;        // unpack tiles in front of the first compute segment
   uint64_t* d_src_off = nullptr;            // [window][3][n_tensors] snapshot offsets of master, m, v (~0: absent)
@@ -126,6 +127,10 @@ struct moev_plan {
           (void)hipEventDestroy(r.done);
         }
         if (r.pinned) (void)hipHostFree(r.pinned);
+      }
+      if (tables_uploaded) {
+        (void)hipEventSynchronize(tables_uploaded);
+        (void)hipEventDestroy(tables_uploaded);
       }
       if (d_tables) (void)hipFree(d_tables);
       if (d_state_ptrs) (void)hipFree(d_state_ptrs);
@@ -204,6 +209,7 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
     MOEV_HIP(hipHostMalloc(&r.pinned, 4ull * h.n_tensors * sizeof(void*), hipHostMallocDefault));
     MOEV_HIP(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
   }
+  MOEV_HIP(hipEventCreateWithFlags(&pl->tables_uploaded, hipEventDisableTiming));
   char* d = pl->d_tables;
   pl->d_segs = reinterpret_cast<moev::SegDesc*>(d + o_segs);
   pl->d_numel = reinterpret_cast<uint64_t*>(d + o_numel);
@@ -260,7 +266,9 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
     }
   }
 
-  // (re)build the scan jobs: they depend on the tile sizes, which moev_tune() may change
+  // (re)build the scan jobs: they depend on the tile sizes, which moev_tune() may change.  An earlier
+  // upload may still be reading the pinned mirror: wait for it before rewriting the jobs.
+  MOEV_HIP(hipEventSynchronize(pl->tables_uploaded));
   const size_t jobs_at = reinterpret_cast<char*>(pl->d_jobs) - pl->d_tables;
   auto* jobs = reinterpret_cast<moev::ScanJob*>(static_cast<char*>(pl->pinned_tables) + jobs_at);
   for (uint32_t k = 0; k < h.window; ++k) {
@@ -287,6 +295,7 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
                                      pl->eff_adam_tile(), h.n_tensors, 1};
   const size_t input_bytes = jobs_at + (2 * h.window + 1) * sizeof(moev::ScanJob);
   MOEV_HIP(hipMemcpyAsync(pl->d_tables, pl->pinned_tables, input_bytes, hipMemcpyHostToDevice, s));
+  MOEV_HIP(hipEventRecord(pl->tables_uploaded, s));
   MOEV_HIP(moev::launch_layout_scan(pl->d_jobs, 2 * h.window + 1, s));
   compute_host_tiles(pl);
   pl->uploaded = true;
