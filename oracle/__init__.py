@@ -23,6 +23,9 @@ _LIB = os.path.join(_HERE, "libmoev_oracle.so")
 MASTER, ADAM_M, ADAM_V, COMPUTE = 0, 1, 2, 3
 HEADER_BYTES = 256
 OK, BAD_ARG, NOT_A_SCHEDULE, TOO_SMALL, BAD_SNAPSHOT = 0, -1, -2, -3, -4
+FMT_F32, FMT_F16, FMT_BF16, FMT_E4M3, FMT_E5M2 = 1, 2, 3, 4, 5
+FMT_BYTES = {FMT_F32: 4, FMT_F16: 2, FMT_BF16: 2, FMT_E4M3: 1, FMT_E5M2: 1}
+FMT_DTYPE = {FMT_F32: np.float32, FMT_F16: np.uint16, FMT_BF16: np.uint16, FMT_E4M3: np.uint8, FMT_E5M2: np.uint8}
 
 
 def build(force: bool = False) -> str:
@@ -78,6 +81,12 @@ def lib():
         _lib.orc_bf16_rne.argtypes = [C.c_float]
         _lib.orc_adam_tensor.restype = None
         _lib.orc_bias_corrections.restype = None
+        _lib.orc_decode.restype = C.c_double
+        _lib.orc_decode.argtypes = [C.c_uint32, C.c_uint32]
+        _lib.orc_encode.restype = C.c_uint32
+        _lib.orc_encode.argtypes = [C.c_uint32, C.c_float]
+        _lib.orc_fmt_bytes.restype = C.c_uint32
+        _lib.orc_fmt_bytes.argtypes = [C.c_uint32]
         _lib.orc_find_window_size.argtypes = [C.c_uint32, C.c_double, C.c_double, C.c_double,
                                               C.c_double, C.c_double, C.POINTER(C.c_uint32),
                                               C.POINTER(C.c_uint32)]
@@ -102,6 +111,7 @@ class Model:
     window: int
     align: int = 256
     widths: Tuple[int, ...] = (4, 4, 4, 2)   # bytes per element: master, Adam m, Adam v, compute
+    formats: Optional[Tuple[int, int, int, int]] = None  # FMT_* per kind (low-precision regimes, Sec. 5.6)
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -316,13 +326,49 @@ def adam_tensor(p, m, v, g, c, hp: AdamHP, step: int) -> None:
                           C.c_uint64(step))
 
 
+def decode(fmt: int, bits: int) -> float:
+    """Value of a bit pattern of storage format `fmt` (Sec. 5.6 regimes)."""
+    return lib().orc_decode(fmt, int(bits))
+
+
+def encode(fmt: int, x: float) -> int:
+    """Bit pattern of the value of format `fmt` nearest to the FP32 number x (ties to even)."""
+    return lib().orc_encode(fmt, C.c_float(x))
+
+
+def adam_tensor_lp(p, m, v, g, c, hp: AdamHP, step: int, formats, scales=(1.0, 1.0, 1.0, 1.0)) -> None:
+    """In-place optimizer step on one tensor stored in `formats` (master, m, v, compute)."""
+    for a, f in zip((p, m, v, c), formats):
+        if a is not None:
+            assert a.dtype == FMT_DTYPE[f] and a.flags["C_CONTIGUOUS"] and a.size == p.size
+    assert g.dtype == np.float32 and g.size == p.size and g.flags["C_CONTIGUOUS"]
+    chp = hp.c()
+    rc = lib().orc_adam_tensor_lp(C.c_void_p(p.ctypes.data), C.c_void_p(m.ctypes.data), C.c_void_p(v.ctypes.data),
+                                  C.c_void_p(g.ctypes.data), None if c is None else C.c_void_p(c.ctypes.data),
+                                  C.c_uint64(p.size), C.byref(chp), C.c_uint64(step),
+                                  (C.c_uint32 * 4)(*formats), (C.c_float * 4)(*scales))
+    if rc:
+        raise OracleError(rc, "adam_tensor_lp")
+
+
 def replay_step(model: Model, hp: AdamHP, step: int, mask: np.ndarray, grads: List[np.ndarray],
-                state: State) -> None:
+                state: State, scales: Optional[np.ndarray] = None) -> None:
+    """scales: float32 array [4, n_tensors] (kind-major) for models with `formats`, or None."""
     assert mask.dtype == np.uint8 and mask.size == model.n_ops
     cm, cs, chp = model.c(), state.c(), hp.c()
     for g, (_, n) in zip(grads, model.tensors):
         assert g.dtype == np.float32 and g.size == n and g.flags["C_CONTIGUOUS"]
     gp = (C.c_void_p * len(grads))(*[g.ctypes.data for g in grads])
+    if model.formats is not None:
+        sp = None
+        if scales is not None:
+            assert scales.dtype == np.float32 and scales.shape == (4, model.n_tensors) and scales.flags["C_CONTIGUOUS"]
+            sp = C.c_void_p(scales.ctypes.data)
+        rc = lib().orc_replay_step_lp(C.byref(cm), (C.c_uint32 * 4)(*model.formats), C.byref(chp), C.c_uint64(step),
+                                      C.c_void_p(mask.ctypes.data), gp, C.byref(cs), sp)
+        if rc:
+            raise OracleError(rc, "replay_step_lp")
+        return
     rc = lib().orc_replay_step(C.byref(cm), C.byref(chp), C.c_uint64(step), C.c_void_p(mask.ctypes.data),
                                gp, C.byref(cs))
     if rc:
@@ -351,11 +397,12 @@ def dense_run(model: Model, state: State, hp: AdamHP, grads_of_step, t0: int, n_
 def poisoned_like(state: State) -> State:
     """A state holding NaN / 0xFFFF patterns everywhere: whatever conversion does not restore shows."""
     out = state.clone()
-    for g in (out.master, out.m, out.v):
+    for g in (out.master, out.m, out.v, out.compute):
         for a in g:
-            a.view(np.uint32)[...] = 0x7FC0DEAD
-    for a in out.compute:
-        a[...] = 0xFFFF
+            if a.dtype == np.float32:
+                a.view(np.uint32)[...] = 0x7FC0DEAD
+            else:
+                a.view(np.uint8)[...] = 0xFF
     return out
 
 

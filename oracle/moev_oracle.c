@@ -426,3 +426,186 @@ int orc_replay_step(const orc_model *mdl, const orc_adam_hp *hp, uint64_t step,
   }
   return ORC_OK;
 }
+
+/* ===================================================================================
+ * Low-precision training state -- Sec. 5.6 evaluates five regimes that store master
+ * weights, optimizer state and compute weights in FP16 or 8-bit floating point instead of
+ * FP32 / 2 bytes.  The paper only names the precisions; readings taken here:
+ *   - FP16 is IEEE binary16 (overflow rounds to infinity); the 8-bit formats are the two
+ *     of the Open Compute Project's 8-bit floating point specification: "E4M3" (bias 7, no
+ *     infinities, one NaN pattern per sign, largest value 448) and "E5M2" (bias 15,
+ *     IEEE-like, largest finite value 57344).  Conversions to them round to nearest even and
+ *     SATURATE: what would exceed the largest finite value, infinities included, becomes
+ *     that value; NaN stays NaN.
+ *   - a stored value may carry a per-tensor scale s (the 8-bit training recipes the paper
+ *     cites keep one per tensor): bits = encode(x * s), x = decode(bits) / s, both in FP32.
+ *     Kinds stored as FP32 ignore their scale.
+ *   - the optimizer step widens the stored state to FP32, performs exactly the FP32 step of
+ *     orc_adam_tensor, and narrows the results; compute weights are cast from the master
+ *     weights AS STORED (after narrowing), not from the unrounded FP32 value.
+ * =================================================================================== */
+
+typedef struct {
+  int exp_bits, man_bits, bias;
+  int ieee_like;   /* 1: all-ones exponent = infinities and NaNs; 0: only all-ones exponent AND mantissa = NaN */
+  int saturate;    /* 1: conversions clamp to the largest finite value */
+} orc_format;
+
+static int format_of(uint32_t fmt, orc_format *f) {
+  switch (fmt) {
+    case ORC_FMT_F16:  *f = (orc_format){5, 10, 15, 1, 0}; return 1;
+    case ORC_FMT_BF16: *f = (orc_format){8, 7, 127, 1, 0}; return 1;
+    case ORC_FMT_E4M3: *f = (orc_format){4, 3, 7, 0, 1}; return 1;
+    case ORC_FMT_E5M2: *f = (orc_format){5, 2, 15, 1, 1}; return 1;
+    default: return 0;
+  }
+}
+
+uint32_t orc_fmt_bytes(uint32_t fmt) {
+  switch (fmt) {
+    case ORC_FMT_F32: return 4;
+    case ORC_FMT_F16: case ORC_FMT_BF16: return 2;
+    case ORC_FMT_E4M3: case ORC_FMT_E5M2: return 1;
+    default: return 0;
+  }
+}
+
+static double largest_finite(const orc_format *f) {
+  int top_exp = (1 << f->exp_bits) - 1;          /* all-ones exponent field */
+  if (f->ieee_like) {                             /* largest finite: exponent field top-1, mantissa all ones */
+    return ldexp((double)((2 << f->man_bits) - 1), top_exp - 1 - f->bias - f->man_bits);
+  }
+  /* all-ones exponent is an ordinary binade; only its all-ones mantissa is NaN */
+  return ldexp((double)((2 << f->man_bits) - 2), top_exp - f->bias - f->man_bits);
+}
+
+/* value of a bit pattern, by the definition of a binary floating-point format:
+ * exponent field 0: mantissa * 2^(1 - bias - man_bits); otherwise (2^man_bits + mantissa) *
+ * 2^(field - bias - man_bits) */
+double orc_decode(uint32_t fmt, uint32_t bits) {
+  if (fmt == ORC_FMT_F32) {
+    float x;
+    memcpy(&x, &bits, 4);
+    return (double)x;
+  }
+  orc_format f;
+  if (!format_of(fmt, &f)) return NAN;
+  uint32_t man = bits & ((1u << f.man_bits) - 1u);
+  uint32_t field = (bits >> f.man_bits) & ((1u << f.exp_bits) - 1u);
+  int negative = (int)((bits >> (f.man_bits + f.exp_bits)) & 1u);
+  uint32_t top = (1u << f.exp_bits) - 1u;
+  double value;
+  if (field == top && f.ieee_like) value = man ? NAN : INFINITY;
+  else if (field == top && man == (1u << f.man_bits) - 1u) value = NAN;
+  else if (field == 0) value = ldexp((double)man, 1 - f.bias - f.man_bits);
+  else value = ldexp((double)((1u << f.man_bits) + man), (int)field - f.bias - f.man_bits);
+  return negative ? -value : value;
+}
+
+/* nearest representable value, ties to the even mantissa; NaN becomes the quiet NaN with all
+ * exponent bits and the top mantissa bit set (E4M3: its only NaN) -- except bfloat16, which keeps
+ * orc_bf16_rne's convention (top 16 bits of the FP32 pattern with the quiet bit set) */
+uint32_t orc_encode(uint32_t fmt, float x) {
+  if (fmt == ORC_FMT_F32) {
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    return bits;
+  }
+  if (fmt == ORC_FMT_BF16) return orc_bf16_rne(x);
+  orc_format f;
+  if (!format_of(fmt, &f)) return 0;
+  uint32_t sign = signbit(x) ? 1u << (f.man_bits + f.exp_bits) : 0u;
+  uint32_t top = (1u << f.exp_bits) - 1u;
+  if (isnan(x)) {
+    if (f.ieee_like) return sign | (top << f.man_bits) | (1u << (f.man_bits - 1));
+    return sign | (top << f.man_bits) | ((1u << f.man_bits) - 1u);
+  }
+  double a = fabs((double)x);
+  double max_finite = largest_finite(&f);
+  double q;  /* the rounded magnitude */
+  if (isinf(x)) q = INFINITY;
+  else if (a == 0.0) q = 0.0;
+  else {
+    int k;
+    frexp(a, &k);                                   /* a = fraction * 2^k, fraction in [0.5, 1) */
+    int binade = k - 1;                             /* 2^binade <= a < 2^(binade+1) */
+    if (binade < 1 - f.bias) binade = 1 - f.bias;   /* subnormals share the spacing of the lowest binade */
+    double spacing = ldexp(1.0, binade - f.man_bits);
+    q = rint(a / spacing) * spacing;                /* default rounding mode: to nearest, ties to even */
+  }
+  if (q > max_finite) {
+    if (f.saturate) q = max_finite;
+    else return sign | (top << f.man_bits);         /* IEEE overflow: infinity */
+  }
+  if (q == 0.0) return sign;
+  int k;
+  frexp(q, &k);
+  int binade = k - 1;
+  if (binade < 1 - f.bias)                          /* subnormal: exponent field 0 */
+    return sign | (uint32_t)ldexp(q, f.bias - 1 + f.man_bits);
+  uint32_t man = (uint32_t)ldexp(q, f.man_bits - binade) - (1u << f.man_bits);
+  return sign | ((uint32_t)(binade + f.bias) << f.man_bits) | man;
+}
+
+static float load_as_fp32(const void *base, uint64_t i, uint32_t fmt, float scale) {
+  if (fmt == ORC_FMT_F32) return ((const float *)base)[i];
+  uint32_t bits = orc_fmt_bytes(fmt) == 2 ? ((const uint16_t *)base)[i] : ((const uint8_t *)base)[i];
+  float stored = (float)orc_decode(fmt, bits);      /* exact: every such value is an FP32 value */
+  return stored / scale;
+}
+
+static void store_from_fp32(void *base, uint64_t i, uint32_t fmt, float scale, float x) {
+  if (fmt == ORC_FMT_F32) {
+    ((float *)base)[i] = x;
+    return;
+  }
+  float scaled = x * scale;
+  uint32_t bits = orc_encode(fmt, scaled);
+  if (orc_fmt_bytes(fmt) == 2) ((uint16_t *)base)[i] = (uint16_t)bits;
+  else ((uint8_t *)base)[i] = (uint8_t)bits;
+}
+
+/*
+ * One optimizer step on a tensor whose state is stored in the given formats
+ * (fmt[kind], scale[kind] with kind = master, m, v, compute).  Gradients are FP32.
+ */
+int orc_adam_tensor_lp(void *p, void *m, void *v, const float *g, void *c, uint64_t n,
+                       const orc_adam_hp *hp, uint64_t step, const uint32_t fmt[4], const float scale[4]) {
+  for (int k = 0; k < 4; ++k)
+    if (orc_fmt_bytes(fmt[k]) == 0) return ORC_BAD_ARG;
+  for (uint64_t i = 0; i < n; ++i) {
+    float param = load_as_fp32(p, i, fmt[ORC_MASTER], scale[ORC_MASTER]);
+    float mom1 = load_as_fp32(m, i, fmt[ORC_ADAM_M], scale[ORC_ADAM_M]);
+    float mom2 = load_as_fp32(v, i, fmt[ORC_ADAM_V], scale[ORC_ADAM_V]);
+    orc_adam_tensor(&param, &mom1, &mom2, g + i, NULL, 1, hp, step);   /* the FP32 step itself */
+    store_from_fp32(p, i, fmt[ORC_MASTER], scale[ORC_MASTER], param);
+    store_from_fp32(m, i, fmt[ORC_ADAM_M], scale[ORC_ADAM_M], mom1);
+    store_from_fp32(v, i, fmt[ORC_ADAM_V], scale[ORC_ADAM_V], mom2);
+    if (c) {
+      float as_stored = load_as_fp32(p, i, fmt[ORC_MASTER], scale[ORC_MASTER]);
+      store_from_fp32(c, i, fmt[ORC_COMPUTE], scale[ORC_COMPUTE], as_stored);
+    }
+  }
+  return ORC_OK;
+}
+
+/* replay step for a model whose state is stored in `fmt`; scales = [4][n_tensors] (kind-major)
+ * or NULL for all ones */
+int orc_replay_step_lp(const orc_model *mdl, const uint32_t fmt[4], const orc_adam_hp *hp, uint64_t step,
+                       const uint8_t *active_mask, const float *const *grads, const orc_state *st,
+                       const float *scales) {
+  if (!mdl || !fmt || !hp || !active_mask || !grads || !st || step == 0) return ORC_BAD_ARG;
+  if (orc_fmt_bytes(fmt[0]) != mdl->width.master || orc_fmt_bytes(fmt[1]) != mdl->width.m ||
+      orc_fmt_bytes(fmt[2]) != mdl->width.v || orc_fmt_bytes(fmt[3]) != mdl->width.compute)
+    return ORC_BAD_ARG;
+  for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
+    if (!active_mask[mdl->tensors[t].op]) continue;
+    float s[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+    if (scales)
+      for (uint32_t k = 0; k < 4; ++k) s[k] = scales[(uint64_t)k * mdl->n_tensors + t];
+    int rc = orc_adam_tensor_lp(st->master[t], st->m[t], st->v[t], grads[t], st->compute[t],
+                                mdl->tensors[t].numel, hp, step, fmt, s);
+    if (rc != ORC_OK) return rc;
+  }
+  return ORC_OK;
+}

@@ -109,6 +109,21 @@ void orc_adam_tensor(float *p, float *m, float *v, const float *g, uint16_t *c, 
 int orc_replay_step(const orc_model *mdl, const orc_adam_hp *hp, uint64_t step,
                     const uint8_t *active_mask, const float *const *grads, const orc_state *st);
 
+/* ---- low-precision training state (Sec. 5.6) ------------------------------------------- */
+/* storage formats of master weights, Adam moments and compute weights in the regimes the paper
+ * evaluates: FP32, FP16 (IEEE binary16), bfloat16 and the two 8-bit formats (4 exponent + 3
+ * mantissa bits without infinities; 5 exponent + 2 mantissa bits, IEEE-like) */
+enum { ORC_FMT_F32 = 1, ORC_FMT_F16 = 2, ORC_FMT_BF16 = 3, ORC_FMT_E4M3 = 4, ORC_FMT_E5M2 = 5 };
+
+uint32_t orc_fmt_bytes(uint32_t fmt);
+double orc_decode(uint32_t fmt, uint32_t bits);
+uint32_t orc_encode(uint32_t fmt, float x);
+int orc_adam_tensor_lp(void *p, void *m, void *v, const float *g, void *c, uint64_t n,
+                       const orc_adam_hp *hp, uint64_t step, const uint32_t fmt[4], const float scale[4]);
+int orc_replay_step_lp(const orc_model *mdl, const uint32_t fmt[4], const orc_adam_hp *hp, uint64_t step,
+                       const uint8_t *active_mask, const float *const *grads, const orc_state *st,
+                       const float *scales);
+
 #ifdef __cplusplus
 }
 #endif

@@ -234,3 +234,47 @@ def random_bits_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, Li
                              generator=_gen(device, stream_seed(seed, 13, t)))
         st["compute"].append(bits.view(torch.bfloat16))
     return st
+
+
+# ---------------------------------------------------------------------------------------
+# low-precision training state (the regimes of Sec. 5.6)
+# ---------------------------------------------------------------------------------------
+# (compute, master, optimizer) precisions of the five evaluated regimes, as torch dtypes in the order
+# master, Adam m, Adam v, compute
+LOW_PRECISION_REGIMES = {
+    "fp16_fp16_fp16+fp16": (torch.float16, torch.float16, torch.float16, torch.float16),
+    "fp8_fp32_fp32+fp32": (torch.float32, torch.float32, torch.float32, torch.float8_e4m3fn),
+    "fp8_fp16_fp32+fp32": (torch.float16, torch.float32, torch.float32, torch.float8_e4m3fn),
+    "fp8_fp16_fp8+fp16": (torch.float16, torch.float8_e4m3fn, torch.float16, torch.float8_e4m3fn),
+    "fp8_fp8_fp8+fp16": (torch.float8_e4m3fn, torch.float8_e4m3fn, torch.float16, torch.float8_e4m3fn),
+}
+
+# per-kind scale that brings the value distributions of make_state into the middle of the narrow
+# formats' ranges (powers of two): master std 0.02, m std 1e-3, v ~1e-6
+DEFAULT_SCALES = {
+    torch.float32: (1.0, 1.0, 1.0, 1.0),
+    torch.float16: (1.0, 64.0, 65536.0, 1.0),
+    torch.bfloat16: (1.0, 1.0, 1.0, 1.0),
+    torch.float8_e4m3fn: (1024.0, 4096.0, 2.0 ** 24, 1024.0),
+    torch.float8_e5m2: (1024.0, 4096.0, 2.0 ** 24, 1024.0),
+}
+
+
+def default_scales(dtypes) -> List[float]:
+    """One scale per kind (master, m, v, compute) for the given storage dtypes."""
+    return [DEFAULT_SCALES[d][k] for k, d in enumerate(dtypes)]
+
+
+def make_low_precision_state(wl: Workload, dtypes, scales, seed: int = 0, device="cpu") -> Dict[str, List[torch.Tensor]]:
+    """The state of make_state stored in the given dtypes: every tensor is multiplied by its kind's
+    scale and cast with torch (any valid bit pattern is a legitimate input; the cast only makes the
+    values plausible).  scales: [4] per kind, or [4][n_tensors]."""
+    st = make_state(wl, seed, device)
+    out: Dict[str, List[torch.Tensor]] = {}
+    for k, kind in enumerate(("master", "m", "v", "compute")):
+        src = st["master"] if kind == "compute" else st[kind]
+        out[kind] = []
+        for t, x in enumerate(src):
+            s = scales[k][t] if isinstance(scales[k], (list, tuple)) else scales[k]
+            out[kind].append((x.float() * float(s)).to(dtypes[k]))
+    return out

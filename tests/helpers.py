@@ -5,8 +5,14 @@ import torch
 import oracle
 
 
-def model_of(wl, align=256, widths=(4, 4, 4, 2)):
-    return oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, align, widths)
+def model_of(wl, align=256, widths=(4, 4, 4, 2), formats=None):
+    if formats is not None:
+        widths = tuple(oracle.FMT_BYTES[f] for f in formats)
+    return oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, align, widths, formats)
+
+
+ORACLE_FMT_OF_DTYPE = {torch.float32: oracle.FMT_F32, torch.float16: oracle.FMT_F16, torch.bfloat16: oracle.FMT_BF16,
+                       torch.float8_e4m3fn: oracle.FMT_E4M3, torch.float8_e5m2: oracle.FMT_E5M2}
 
 
 def hp_of(wl):
@@ -15,8 +21,10 @@ def hp_of(wl):
 
 def np_of(t: torch.Tensor) -> np.ndarray:
     t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16).copy()
+    if t.dtype in (torch.float8_e4m3fn, torch.float8_e5m2):
+        return t.view(torch.uint8).numpy().copy()
     return t.numpy().copy()
 
 
