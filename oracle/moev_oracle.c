@@ -438,7 +438,8 @@ int orc_replay_step(const orc_model *mdl, const orc_adam_hp *hp, uint64_t step,
  *     SATURATE: what would exceed the largest finite value, infinities included, becomes
  *     that value; NaN stays NaN.
  *   - a stored value may carry a per-tensor scale s (the 8-bit training recipes the paper
- *     cites keep one per tensor): bits = encode(x * s), x = decode(bits) / s, both in FP32.
+ *     cites keep one per tensor together with its reciprocal): bits = encode(x * s),
+ *     x = decode(bits) * (1 / s), every operation in FP32 (the reciprocal is rounded once).
  *     Kinds stored as FP32 ignore their scale.
  *   - the optimizer step widens the stored state to FP32, performs exactly the FP32 step of
  *     orc_adam_tensor, and narrows the results; compute weights are cast from the master
@@ -548,10 +549,11 @@ uint32_t orc_encode(uint32_t fmt, float x) {
 }
 
 static float load_as_fp32(const void *base, uint64_t i, uint32_t fmt, float scale) {
+  float reciprocal = 1.0f / scale;
   if (fmt == ORC_FMT_F32) return ((const float *)base)[i];
   uint32_t bits = orc_fmt_bytes(fmt) == 2 ? ((const uint16_t *)base)[i] : ((const uint8_t *)base)[i];
   float stored = (float)orc_decode(fmt, bits);      /* exact: every such value is an FP32 value */
-  return stored / scale;
+  return stored * reciprocal;
 }
 
 static void store_from_fp32(void *base, uint64_t i, uint32_t fmt, float scale, float x) {

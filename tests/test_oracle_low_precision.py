@@ -199,7 +199,7 @@ def test_fp32_formats_reduce_to_the_fp32_step():
 @pytest.mark.parametrize("regime", list(REGIMES))
 @pytest.mark.parametrize("scales", [(1.0, 1.0, 1.0, 1.0), (1024.0, 4096.0, 65536.0, 512.0), (3.0, 1000.0, 12345.0, 0.7)])
 def test_low_precision_step_is_widen_step_narrow(regime, scales):
-    """The step equals: decode every stored value (pinned above), divide by the scale, take the FP32
+    """The step equals: decode every stored value (pinned above), multiply by the scale's reciprocal, take the FP32
     step (pinned in test_oracle_adam_conversion), multiply by the scale, encode; compute weights from
     the master weights as stored.  Composed here element by element from the separately pinned pieces."""
     fmts = REGIMES[regime]
@@ -221,7 +221,7 @@ def test_low_precision_step_is_widen_step_narrow(regime, scales):
     def widen(arr, k, i):
         if fmts[k] == F32:
             return f32(arr[i])
-        return f32(f32(oracle.decode(fmts[k], int(arr[i]))) / f32(scales[k]))
+        return f32(f32(oracle.decode(fmts[k], int(arr[i]))) * (f32(1) / f32(scales[k])))
 
     def narrow(k, x):
         if fmts[k] == F32:
