@@ -63,6 +63,16 @@ enum {
 
 enum { MOEV_KIND_MASTER = 0, MOEV_KIND_ADAM_M = 1, MOEV_KIND_ADAM_V = 2, MOEV_KIND_COMPUTE = 3 };
 
+/* storage formats of the training state (the low-precision regimes of Sec. 5.6 keep master weights,
+ * optimizer state and compute weights in FP16 or 8-bit floating point):
+ *   F32  IEEE binary32          F16  IEEE binary16          BF16  upper half of binary32
+ *   E4M3 8 bits, 4 exponent (bias 7) + 3 mantissa, no infinities, NaN = S.1111.111, largest value 448
+ *   E5M2 8 bits, 5 exponent (bias 15) + 2 mantissa, IEEE-like, largest finite value 57344
+ * Conversions round to nearest even.  F16 and BF16 overflow to infinity; E4M3 and E5M2 saturate
+ * (anything beyond the largest finite value, infinities included, becomes that value); NaN stays NaN
+ * (F16 0x7e00, E5M2 0x7e, E4M3 0x7f, with the sign; BF16 keeps the top 16 bits with the quiet bit set). */
+enum { MOEV_FMT_DEFAULT = 0, MOEV_FMT_F32 = 1, MOEV_FMT_F16 = 2, MOEV_FMT_BF16 = 3, MOEV_FMT_E4M3 = 4, MOEV_FMT_E5M2 = 5 };
+
 enum {
   MOEV_EXPLICIT = 0, /* slot_of_op given by the caller */
   MOEV_FIXED = 1,    /* GenerateSchedule of Algorithm 1 from `order` and `n_active` */
@@ -96,7 +106,11 @@ typedef struct {
   uint8_t master_bytes;        /* element widths in bytes (1, 2, 4 or 8); 0 = defaults 4, 4, 4, 2.  Other */
   uint8_t m_bytes;             /* values describe the low-precision regimes of Sec. 5.6 (e.g. FP8 master, */
   uint8_t v_bytes;             /* FP8 + FP16 moments, FP8 compute = 1, 1, 2, 1): pack, drain and unpack */
-  uint8_t compute_bytes;       /* are byte copies and work for any widths; the replay needs 4, 4, 4, 2 */
+  uint8_t compute_bytes;       /* are byte copies and work for any widths */
+  uint8_t master_fmt;          /* MOEV_FMT_* of each kind, used by the replay only.  0 = by width: 4 -> F32, */
+  uint8_t m_fmt;               /* 2 -> F16 (compute weights: BF16), 1 -> E4M3, 8 -> none (no replay).  A format */
+  uint8_t v_fmt;               /* given with width 0 sets the width; a format that contradicts a given width */
+  uint8_t compute_fmt;         /* is MOEV_E_INVAL. */
 } moev_plan_cfg;
 
 typedef struct {
@@ -120,6 +134,10 @@ typedef struct {
 typedef struct {
   float lr, beta1, beta2, eps, weight_decay;
   uint64_t step;
+  const float *d_scales; /* device, [4][n_tensors] kind-major (master, m, v, compute), or NULL = all 1:
+                            per-tensor scale s of the kinds stored narrower than FP32, bits = encode(x * s),
+                            x = decode(bits) * (1 / s) in FP32.  Kinds stored as FP32 ignore theirs.  The
+                            array must stay valid until the replay has run. */
 } moev_adam;
 
 typedef struct {
@@ -197,6 +215,9 @@ uint32_t ckpt_plan_n_ops(const moev_plan *plan);
 uint32_t ckpt_plan_n_tensors(const moev_plan *plan);
 uint32_t ckpt_plan_n_active(const moev_plan *plan);            /* O_Active (0 for EXPLICIT) */
 uint64_t ckpt_plan_hash(const moev_plan *plan);
+/* element width in bytes / MOEV_FMT_* (0: none, the kind is only ever copied) of a MOEV_KIND_*; 0 on bad arguments */
+uint32_t ckpt_plan_width(const moev_plan *plan, uint32_t kind);
+uint32_t ckpt_plan_format(const moev_plan *plan, uint32_t kind);
 int ckpt_plan_slot_of_op(const moev_plan *plan, uint32_t *out /* host [n_ops] */);
 int ckpt_plan_order(const moev_plan *plan, uint32_t *out /* host [n_ops] */);
 uint64_t ckpt_plan_packed_bytes(const moev_plan *plan, uint32_t slot); /* 0 if slot >= window */
@@ -270,7 +291,12 @@ int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d
  *     compute = bf16(p)
  * all in FP32, every operation rounded separately (no fused multiply-add), division and
  * square root correctly rounded.  Tensors of frozen operators are not touched.
- * Requires element widths 4, 4, 2.  Errors: MOEV_E_INVAL, MOEV_E_HIP. */
+ * State stored in other formats than FP32 / FP32 / FP32 / BF16 (Sec. 5.6) is widened to FP32
+ * (decode, times the reciprocal of its scale), takes exactly the step above, and is narrowed
+ * again (times the scale, encode); the compute weights are then cast from the master weights
+ * AS STORED.  Supported width combinations (master, m, v, compute): 4,4,4,2  2,2,2,2  4,4,4,1
+ * 2,4,4,1  2,1,2,1  1,1,2,1 with any format of that width; others are MOEV_E_INVAL.
+ * Errors: MOEV_E_INVAL, MOEV_E_HIP. */
 int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
                    void *const *grads, const moev_state *state, void *stream);
 
@@ -280,6 +306,7 @@ int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_acti
  * buffer by the replay kernel instead of being scattered to the dense tensors and read back
  * (26 fewer bytes of HBM traffic per newly active parameter).  Arguments as in the two calls;
  * d_active_mask is updated like restore_unpack does and then used like convert_replay does.
+ * For state in other formats than FP32 / FP32 / FP32 / BF16 the two kernels run unfused.
  * Every tensor of an operator active in `slot` must have a gradient (MOEV_E_INVAL otherwise).
  * A foreign device-resident snapshot is refused as a whole (status word, nothing is modified). */
 int convert_window_step(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d_packed,

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmoev.so")
 OK, E_INVAL, E_NOMEM, E_RANGE, E_MISMATCH, E_HIP = 0, -1, -2, -3, -4, -5
 KIND_MASTER, KIND_ADAM_M, KIND_ADAM_V, KIND_COMPUTE = 0, 1, 2, 3
 EXPLICIT, FIXED, AUTO = 0, 1, 2
+FMT_DEFAULT, FMT_F32, FMT_F16, FMT_BF16, FMT_E4M3, FMT_E5M2 = range(6)
 HEADER_BYTES = 256
 (TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL,
  TUNE_PERSISTENT, TUNE_COPY_THREADS, TUNE_COPY_UNROLL, TUNE_ADAM_THREADS, TUNE_ADAM_UNROLL,
@@ -26,7 +27,7 @@ EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",
     "moev_reorder_needed", "moev_popularity_time_decayed", "moev_popularity_capacity_aware", "moev_ettr",
     "moev_recovery_time", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
-    "ckpt_plan_hash", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
+    "ckpt_plan_hash", "ckpt_plan_width", "ckpt_plan_format", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
     "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
@@ -50,7 +51,8 @@ class _PlanCfg(C.Structure):
                 ("mode", C.c_int), ("window", C.c_uint32), ("n_active", C.c_uint32),
                 ("order", C.POINTER(C.c_uint32)), ("slot_of_op", C.POINTER(C.c_uint32)),
                 ("t_iter_s", C.c_double), ("host_link_Bps", C.c_double), ("align", C.c_uint32),
-                ("master_bytes", C.c_uint8), ("m_bytes", C.c_uint8), ("v_bytes", C.c_uint8), ("compute_bytes", C.c_uint8)]
+                ("master_bytes", C.c_uint8), ("m_bytes", C.c_uint8), ("v_bytes", C.c_uint8), ("compute_bytes", C.c_uint8),
+                ("master_fmt", C.c_uint8), ("m_fmt", C.c_uint8), ("v_fmt", C.c_uint8), ("compute_fmt", C.c_uint8)]
 
 
 class _Segment(C.Structure):
@@ -64,7 +66,7 @@ class _State(C.Structure):
 
 class _Adam(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("step", C.c_uint64)]
+                ("weight_decay", C.c_float), ("step", C.c_uint64), ("d_scales", C.c_void_p)]
 
 
 class _Header(C.Structure):
@@ -98,6 +100,9 @@ def _load():
         getattr(lib, name).restype = u32
     lib.ckpt_plan_hash.argtypes = [vp]
     lib.ckpt_plan_hash.restype = u64
+    for name in ("ckpt_plan_width", "ckpt_plan_format"):
+        getattr(lib, name).argtypes = [vp, u32]
+        getattr(lib, name).restype = u32
     lib.ckpt_plan_slot_of_op.argtypes = [vp, C.POINTER(u32)]
     lib.ckpt_plan_order.argtypes = [vp, C.POINTER(u32)]
     lib.ckpt_plan_packed_bytes.argtypes = [vp, u32]
@@ -246,7 +251,7 @@ class Plan:
 def ckpt_plan(tensors: Sequence, mode: int = EXPLICIT, window: int = 0, n_active: int = 0,
               order: Optional[Sequence[int]] = None, slot_of_op: Optional[Sequence[int]] = None,
               t_iter_s: float = 0.0, host_link_Bps: float = 0.0, align: int = 0,
-              widths=(0, 0, 0, 0), n_ops: Optional[int] = None) -> Plan:
+              widths=(0, 0, 0, 0), n_ops: Optional[int] = None, formats=(0, 0, 0, 0)) -> Plan:
     nt = len(tensors)
     if n_ops is None:
         n_ops = (max(op for op, _ in tensors) + 1) if nt else 0
@@ -256,7 +261,7 @@ def ckpt_plan(tensors: Sequence, mode: int = EXPLICIT, window: int = 0, n_active
     if len(widths) == 3:  # (master, both moments, compute)
         widths = (widths[0], widths[1], widths[1], widths[2])
     cfg = _PlanCfg(n_ops, nt, ts, mode, window, n_active, order_a, slots_a, t_iter_s, host_link_Bps, align,
-                   widths[0], widths[1], widths[2], widths[3])
+                   widths[0], widths[1], widths[2], widths[3], formats[0], formats[1], formats[2], formats[3])
     out = C.c_void_p()
     _check(_lib.ckpt_plan(C.byref(cfg), C.byref(out)))
     return Plan(out.value)
@@ -273,6 +278,8 @@ def ckpt_plan_n_ops(plan): return _lib.ckpt_plan_n_ops(plan.handle)
 def ckpt_plan_n_tensors(plan): return _lib.ckpt_plan_n_tensors(plan.handle)
 def ckpt_plan_n_active(plan): return _lib.ckpt_plan_n_active(plan.handle)
 def ckpt_plan_hash(plan): return _lib.ckpt_plan_hash(plan.handle)
+def ckpt_plan_width(plan, kind): return _lib.ckpt_plan_width(plan.handle, kind)
+def ckpt_plan_format(plan, kind): return _lib.ckpt_plan_format(plan.handle, kind)
 def ckpt_plan_packed_bytes(plan, slot): return _lib.ckpt_plan_packed_bytes(plan.handle, slot)
 def ckpt_plan_max_packed_bytes(plan): return _lib.ckpt_plan_max_packed_bytes(plan.handle)
 def ckpt_plan_n_segments(plan, slot): return _lib.ckpt_plan_n_segments(plan.handle, slot)
@@ -352,16 +359,16 @@ def restore_unpack(plan, slot: int, h_pinned, d_packed, state: State, d_active_m
 
 
 def convert_replay(plan, lr, beta1, beta2, eps, weight_decay, step: int, d_active_mask, grads: Sequence,
-                   state: State, stream=None):
-    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step)
+                   state: State, stream=None, d_scales=None):
+    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step, _addr(d_scales))
     g = _ptr_array(grads)
     _check(_lib.convert_replay(plan.handle, C.byref(adam), _addr(d_active_mask), g, C.byref(state.c),
                                _stream(stream)))
 
 
 def convert_window_step(plan, slot: int, h_pinned, d_packed, lr, beta1, beta2, eps, weight_decay, step: int,
-                        d_active_mask, grads: Sequence, state: State, stream=None):
-    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step)
+                        d_active_mask, grads: Sequence, state: State, stream=None, d_scales=None):
+    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step, _addr(d_scales))
     g = _ptr_array(grads)
     _check(_lib.convert_window_step(plan.handle, slot, _addr(h_pinned), _addr(d_packed), C.byref(adam),
                                     _addr(d_active_mask), g, C.byref(state.c), _stream(stream)))

@@ -17,6 +17,10 @@
 #include "moev.h"
 #include "plan.hpp"
 
+static_assert(moev::kFmtF32 == MOEV_FMT_F32 && moev::kFmtF16 == MOEV_FMT_F16 && moev::kFmtBF16 == MOEV_FMT_BF16 &&
+                  moev::kFmtE4M3 == MOEV_FMT_E4M3 && moev::kFmtE5M2 == MOEV_FMT_E5M2,
+              "the kernels' format numbers are the interface's");
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -404,6 +408,17 @@ int check_slot_pointers(const moev_plan* pl, uint32_t slot, const moev_state* st
   return MOEV_OK;
 }
 
+// FP32 master weights and moments, bfloat16 compute weights: the regime of the specialised kernels
+bool fp32_regime(const moev::HostPlan& h) {
+  return h.fmt[MOEV_KIND_MASTER] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_ADAM_M] == MOEV_FMT_F32 &&
+         h.fmt[MOEV_KIND_ADAM_V] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_COMPUTE] == MOEV_FMT_BF16;
+}
+// restore_unpack re-derives the compute weights of newly active operators in this case only; in the
+// other regimes the replay step that follows the load writes them
+bool derives_compute(const moev::HostPlan& h) {
+  return h.fmt[MOEV_KIND_MASTER] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_COMPUTE] == MOEV_FMT_BF16;
+}
+
 int check_unpack_args(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_state* state,
                       const char* who) {
   if (!p || !d_packed) return fail(MOEV_E_INVAL, "%s: null argument", who);
@@ -412,7 +427,7 @@ int check_unpack_args(moev_plan* p, uint32_t slot, const void* h_pinned, void* d
   int rc = check_state(p, state, who);
   if (rc != MOEV_OK) return rc;
   const auto& h = p->host;
-  const bool derive = h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2;
+  const bool derive = derives_compute(h);
   rc = check_slot_pointers(p, slot, state, derive, who);
   if (rc != MOEV_OK) return rc;
   if (h_pinned) {
@@ -435,7 +450,7 @@ int launch_unpack_locked(moev_plan* p, uint32_t slot, const void* h_pinned, void
     MOEV_HIP(hipMemcpyAsync(d_packed, h_pinned, h.slots[slot].packed_bytes, hipMemcpyHostToDevice, s));
   moev::CopyArgs a = copy_args(p, slot, 0, d_packed, true);
   a.mask = d_active_mask;
-  a.derive_compute = (h.width[MOEV_KIND_MASTER] == 4 && h.width[MOEV_KIND_COMPUTE] == 2) ? 1u : 0u;
+  a.derive_compute = derives_compute(h) ? 1u : 0u;
   if (p->persistent) {
     MOEV_HIP(moev::launch_unpack_persistent(a, grid_for(p, p->slot_tiles_unpack[slot], p->copy_max_blocks), p->nontemporal != 0, s));
   } else {
@@ -451,9 +466,15 @@ int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_acti
                       const moev_state* state, const char* who) {
   if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "%s: null argument", who);
   const auto& h = p->host;
-  if (h.width[MOEV_KIND_MASTER] != 4 || h.width[MOEV_KIND_ADAM_M] != 4 || h.width[MOEV_KIND_ADAM_V] != 4 ||
-      h.width[MOEV_KIND_COMPUTE] != 2)
-    return fail(MOEV_E_INVAL, "%s: needs FP32 master and moments and 2-byte compute weights", who);
+  if (!fp32_regime(h)) {
+    if (!h.fmt[0] || !h.fmt[1] || !h.fmt[2] || !h.fmt[3] || !moev::lp_widths_supported(h.width))
+      return fail(MOEV_E_INVAL, "%s: no replay kernel for element widths %u, %u, %u, %u", who, h.width[0], h.width[1],
+                  h.width[2], h.width[3]);
+    if (!p->persistent && !moev::lp_shape_supported(static_cast<uint32_t>(p->adam_threads), static_cast<uint32_t>(p->adam_unroll)))
+      return fail(MOEV_E_INVAL, "%s: the low-precision replay runs with 64, 128 or 256 threads and unroll 1, 2 or 4", who);
+    if (adam->d_scales && (reinterpret_cast<uintptr_t>(adam->d_scales) & 3u))
+      return fail(MOEV_E_INVAL, "%s: d_scales is not 4-byte aligned", who);
+  }
   if (adam->step == 0) return fail(MOEV_E_INVAL, "%s: step counts from 1", who);
   int rc = check_state(p, state, who);
   if (rc != MOEV_OK) return rc;
@@ -503,9 +524,18 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
   a.decay = adam->lr * adam->weight_decay;
   a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
-  if (p->persistent) {
+  const bool low_precision = !fp32_regime(h);
+  if (p->persistent && !low_precision) {
     MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
     return MOEV_OK;
+  }
+  // (state in other formats than FP32 / FP32 / FP32 / BF16 has the one-tile-per-workgroup shape only)
+  uint32_t threads = static_cast<uint32_t>(p->adam_threads), unroll = static_cast<uint32_t>(p->adam_unroll);
+  if (p->persistent) {
+    threads = 256;
+    unroll = 1;
+    a.tile_elems = threads * 4 * unroll;
+    a.lds_entries = 0;
   }
   // The device compacts the tile list to the tensors that are active (mask) and have gradients;
   // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles.
@@ -521,9 +551,12 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
     fill_header(p, static_cast<uint32_t>(fused_slot), 0, a.header);
     MOEV_HIP(moev::launch_adam_fused(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
                                      static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
+  } else if (low_precision) {
+    a.scales = adam->d_scales;
+    for (int k = 0; k < 4; ++k) a.fmt[k] = h.fmt[k];
+    MOEV_HIP(moev::launch_adam_lp(a, h.width, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   } else {
-    MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), static_cast<uint32_t>(p->adam_threads),
-                                      static_cast<uint32_t>(p->adam_unroll), p->nontemporal != 0, s));
+    MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   }
   return MOEV_OK;
 }
@@ -636,6 +669,8 @@ uint32_t ckpt_plan_window(const moev_plan* p) { return p ? p->host.window : 0; }
 uint32_t ckpt_plan_n_ops(const moev_plan* p) { return p ? p->host.n_ops : 0; }
 uint32_t ckpt_plan_n_tensors(const moev_plan* p) { return p ? p->host.n_tensors : 0; }
 uint32_t ckpt_plan_n_active(const moev_plan* p) { return p ? p->host.n_active : 0; }
+uint32_t ckpt_plan_width(const moev_plan* p, uint32_t kind) { return (p && kind < 4) ? p->host.width[kind] : 0; }
+uint32_t ckpt_plan_format(const moev_plan* p, uint32_t kind) { return (p && kind < 4) ? p->host.fmt[kind] : 0; }
 uint64_t ckpt_plan_hash(const moev_plan* p) { return p ? p->host.hash : 0; }
 
 int ckpt_plan_slot_of_op(const moev_plan* p, uint32_t* out) {
@@ -923,7 +958,7 @@ int convert_window_step(moev_plan* p, uint32_t slot, const void* h_pinned, void*
       return fail(MOEV_E_INVAL, "convert_window_step: tensor %u becomes active in slot %u but has no gradient", t, slot);
   std::lock_guard<std::mutex> lock(p->mu);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool fused = !p->persistent;
+  const bool fused = !p->persistent && fp32_regime(h);
   rc = launch_unpack_locked(p, slot, h_pinned, d_packed, state, d_active_mask, s, fused);
   if (rc != MOEV_OK) return rc;
   return launch_replay_locked(p, adam, d_active_mask, grads, state, s, fused ? static_cast<int>(slot) : -1, d_packed);

@@ -61,6 +61,9 @@ struct AdamArgs {
   uint64_t header[7];
   uint32_t n_tensors, tile_elems, lds_entries, has_decay;
   uint32_t xcd_regions;        // as in CopyArgs
+  // state stored in other formats than FP32 / FP32 / FP32 / BF16 (k_adam_lp only)
+  const float* scales;         // [4 * n_tensors] kind-major per-tensor scales, or null = all 1
+  uint32_t fmt[4];             // kFmt* of master, m, v, compute
   float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
 };
 
@@ -80,10 +83,20 @@ hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threa
 hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
                              hipStream_t s);
 
+// Replay on state stored in narrow formats: `width` = bytes per element of master, m, v, compute.
+// Same tile list and grid as launch_adam_direct (tile = threads * 4 elements * unroll).
+bool lp_widths_supported(const uint8_t width[4]);
+bool lp_shape_supported(uint32_t threads, uint32_t unroll);
+hipError_t launch_adam_lp(const AdamArgs& a, const uint8_t width[4], uint32_t blocks, uint32_t threads, uint32_t unroll,
+                          bool nt, hipStream_t s);
+
 // fixed grid of 256-thread workgroups walking the tile list
 hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);
 hipError_t launch_unpack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);
 hipError_t launch_adam_persistent(const AdamArgs& a, uint32_t blocks, bool nt, hipStream_t s);
+
+// storage formats (same values as the C interface's MOEV_FMT_*)
+constexpr uint32_t kFmtF32 = 1, kFmtF16 = 2, kFmtBF16 = 3, kFmtE4M3 = 4, kFmtE5M2 = 5;
 
 constexpr uint32_t kThreads = 256;           // 4 wavefronts of 64
 constexpr uint32_t kMaxLdsEntries = 8192;    // 32 KB of tile_start in LDS at most; larger tables are searched in global memory

@@ -68,15 +68,30 @@ int build_plan(const moev_plan_cfg& cfg, HostPlan& p, std::string& err) {
     err = "ckpt_plan: align must be a power of two in [16, 2^24]";
     return MOEV_E_INVAL;
   }
-  p.width[MOEV_KIND_MASTER] = cfg.master_bytes ? cfg.master_bytes : 4;
-  p.width[MOEV_KIND_ADAM_M] = cfg.m_bytes ? cfg.m_bytes : 4;
-  p.width[MOEV_KIND_ADAM_V] = cfg.v_bytes ? cfg.v_bytes : 4;
-  p.width[MOEV_KIND_COMPUTE] = cfg.compute_bytes ? cfg.compute_bytes : 2;
-  for (uint8_t w : p.width)
+  // element widths and storage formats (Sec. 5.6 regimes); either may be left to the other
+  const uint8_t widths_in[4] = {cfg.master_bytes, cfg.m_bytes, cfg.v_bytes, cfg.compute_bytes};
+  const uint8_t fmts_in[4] = {cfg.master_fmt, cfg.m_fmt, cfg.v_fmt, cfg.compute_fmt};
+  for (int k = 0; k < 4; ++k) {
+    uint8_t w = widths_in[k], f = fmts_in[k];
+    if (f > MOEV_FMT_E5M2) {
+      err = "ckpt_plan: unknown storage format";
+      return MOEV_E_INVAL;
+    }
+    const uint8_t w_of_f = f == MOEV_FMT_F32 ? 4 : (f == MOEV_FMT_F16 || f == MOEV_FMT_BF16) ? 2 : f ? 1 : 0;
+    if (w == 0) w = w_of_f ? w_of_f : (k == MOEV_KIND_COMPUTE ? 2 : 4);
     if (w != 1 && w != 2 && w != 4 && w != 8) {
       err = "ckpt_plan: element widths must be 1, 2, 4 or 8 bytes";
       return MOEV_E_INVAL;
     }
+    if (f == MOEV_FMT_DEFAULT)
+      f = w == 4 ? MOEV_FMT_F32 : w == 2 ? (k == MOEV_KIND_COMPUTE ? MOEV_FMT_BF16 : MOEV_FMT_F16) : w == 1 ? MOEV_FMT_E4M3 : 0;
+    else if (w_of_f != w) {
+      err = "ckpt_plan: storage format does not have the given element width";
+      return MOEV_E_INVAL;
+    }
+    p.width[k] = w;
+    p.fmt[k] = f;
+  }
 
   // tensors: grouped by operator, operators ascending from 0, every operator present
   p.tensors.assign(cfg.tensors, cfg.tensors + cfg.n_tensors);

@@ -19,6 +19,7 @@ struct HostSlot {
 struct HostPlan {
   uint32_t n_ops = 0, n_tensors = 0, window = 0, n_active = 0, align = 256;
   uint8_t width[4] = {4, 4, 4, 2};            // bytes per element, indexed by MOEV_KIND_*
+  uint8_t fmt[4] = {MOEV_FMT_F32, MOEV_FMT_F32, MOEV_FMT_F32, MOEV_FMT_BF16};  // MOEV_FMT_*, 0 = copy only
   std::vector<moev_tensor> tensors;
   std::vector<uint32_t> order;                 // O_Ordered
   std::vector<uint32_t> slot_of_op;

@@ -102,6 +102,30 @@ def test_low_precision_layouts_match_oracle(orc, widths):
         assert round(100 * (1 - full / 12)) in (66, 67)
 
 
+def test_storage_formats_and_widths_resolve_each_other():
+    """Formats and widths of the Sec. 5.6 regimes: either may be left to the other; a contradiction is refused."""
+    tensors = [(0, 10), (1, 20)]
+    kw = dict(mode=B.EXPLICIT, window=2, slot_of_op=[0, 1])
+    plan = B.ckpt_plan(tensors, **kw)
+    assert [B.ckpt_plan_width(plan, k) for k in range(4)] == [4, 4, 4, 2]
+    assert [B.ckpt_plan_format(plan, k) for k in range(4)] == [B.FMT_F32, B.FMT_F32, B.FMT_F32, B.FMT_BF16]
+    plan = B.ckpt_plan(tensors, widths=(1, 1, 2, 1), **kw)   # widths only: FP16 for 2 bytes, E4M3 for 1 byte
+    assert [B.ckpt_plan_format(plan, k) for k in range(4)] == [B.FMT_E4M3, B.FMT_E4M3, B.FMT_F16, B.FMT_E4M3]
+    plan = B.ckpt_plan(tensors, widths=(2, 2, 2, 2), **kw)   # 2-byte compute weights default to bfloat16
+    assert [B.ckpt_plan_format(plan, k) for k in range(4)] == [B.FMT_F16, B.FMT_F16, B.FMT_F16, B.FMT_BF16]
+    plan = B.ckpt_plan(tensors, formats=(B.FMT_F16, B.FMT_E5M2, B.FMT_BF16, B.FMT_E4M3), **kw)  # formats only
+    assert [B.ckpt_plan_width(plan, k) for k in range(4)] == [2, 1, 2, 1]
+    assert [B.ckpt_plan_format(plan, k) for k in range(4)] == [B.FMT_F16, B.FMT_E5M2, B.FMT_BF16, B.FMT_E4M3]
+    plan = B.ckpt_plan(tensors, widths=(8, 8, 8, 8), **kw)   # copy-only state: no format
+    assert [B.ckpt_plan_format(plan, k) for k in range(4)] == [0, 0, 0, 0]
+    assert B.ckpt_plan_width(plan, 4) == 0 and B.ckpt_plan_format(plan, 7) == 0
+    for bad in (dict(widths=(4, 4, 4, 2), formats=(B.FMT_F16, 0, 0, 0)), dict(formats=(0, 0, 0, 6)),
+                dict(widths=(3, 4, 4, 2))):
+        with pytest.raises(B.MoevError) as e:
+            B.ckpt_plan(tensors, **kw, **bad)
+        assert e.value.code == B.E_INVAL
+
+
 def test_fixed_mode_matches_generate_schedule(orc):
     for n, a, seed in [(6, 2, 0), (13, 4, 1), (8, 1, 2), (66, 66, 3), (7, 3, 4)]:
         order = W.seeded_permutation(n, seed)
