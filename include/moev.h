@@ -70,7 +70,7 @@ enum { MOEV_KIND_MASTER = 0, MOEV_KIND_ADAM_M = 1, MOEV_KIND_ADAM_V = 2, MOEV_KI
  *   E5M2 8 bits, 5 exponent (bias 15) + 2 mantissa, IEEE-like, largest finite value 57344
  * Conversions round to nearest even.  F16 and BF16 overflow to infinity; E4M3 and E5M2 saturate
  * (anything beyond the largest finite value, infinities included, becomes that value); NaN stays NaN
- * (F16 0x7e00, E5M2 0x7e, E4M3 0x7f, with the sign; BF16 keeps the top 16 bits with the quiet bit set). */
+ * (which of the format's NaN patterns is written is not specified). */
 enum { MOEV_FMT_DEFAULT = 0, MOEV_FMT_F32 = 1, MOEV_FMT_F16 = 2, MOEV_FMT_BF16 = 3, MOEV_FMT_E4M3 = 4, MOEV_FMT_E5M2 = 5 };
 
 enum {
@@ -294,8 +294,12 @@ int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d
  * State stored in other formats than FP32 / FP32 / FP32 / BF16 (Sec. 5.6) is widened to FP32
  * (decode, times the reciprocal of its scale), takes exactly the step above, and is narrowed
  * again (times the scale, encode); the compute weights are then cast from the master weights
- * AS STORED.  Supported width combinations (master, m, v, compute): 4,4,4,2  2,2,2,2  4,4,4,1
- * 2,4,4,1  2,1,2,1  1,1,2,1 with any format of that width; others are MOEV_E_INVAL.
+ * AS STORED.  Format combinations with a kernel (master, m, v, compute): the five regimes of
+ * Sec. 5.6  F16 F16 F16 F16 | F32 F32 F32 E4M3 | F16 F32 F32 E4M3 | F16 E4M3 F16 E4M3 |
+ * E4M3 E4M3 F16 E4M3,  FP32 state with FP16 compute weights  F32 F32 F32 F16,  and
+ * F16 F16 F16 BF16 | BF16 BF16 BF16 BF16 | F16 E5M2 F16 E5M2 | E5M2 E4M3 BF16 E5M2;
+ * others are MOEV_E_INVAL.  These regimes run with 64, 128 or 256 threads and unroll 1 or 2
+ * (MOEV_TUNE_ADAM_*), one tile per workgroup.
  * Errors: MOEV_E_INVAL, MOEV_E_HIP. */
 int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
                    void *const *grads, const moev_state *state, void *stream);

@@ -467,11 +467,11 @@ int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_acti
   if (!p || !adam || !d_active_mask || !grads) return fail(MOEV_E_INVAL, "%s: null argument", who);
   const auto& h = p->host;
   if (!fp32_regime(h)) {
-    if (!h.fmt[0] || !h.fmt[1] || !h.fmt[2] || !h.fmt[3] || !moev::lp_widths_supported(h.width))
-      return fail(MOEV_E_INVAL, "%s: no replay kernel for element widths %u, %u, %u, %u", who, h.width[0], h.width[1],
-                  h.width[2], h.width[3]);
+    if (!moev::lp_formats_supported(h.fmt))
+      return fail(MOEV_E_INVAL, "%s: no replay kernel for storage formats %u, %u, %u, %u (master, m, v, compute)", who,
+                  h.fmt[0], h.fmt[1], h.fmt[2], h.fmt[3]);
     if (!p->persistent && !moev::lp_shape_supported(static_cast<uint32_t>(p->adam_threads), static_cast<uint32_t>(p->adam_unroll)))
-      return fail(MOEV_E_INVAL, "%s: the low-precision replay runs with 64, 128 or 256 threads and unroll 1, 2 or 4", who);
+      return fail(MOEV_E_INVAL, "%s: the low-precision replay runs with 64, 128 or 256 threads and unroll 1 or 2", who);
     if (adam->d_scales && (reinterpret_cast<uintptr_t>(adam->d_scales) & 3u))
       return fail(MOEV_E_INVAL, "%s: d_scales is not 4-byte aligned", who);
   }
@@ -554,7 +554,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   } else if (low_precision) {
     a.scales = adam->d_scales;
     for (int k = 0; k < 4; ++k) a.fmt[k] = h.fmt[k];
-    MOEV_HIP(moev::launch_adam_lp(a, h.width, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
+    MOEV_HIP(moev::launch_adam_lp(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   } else {
     MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   }

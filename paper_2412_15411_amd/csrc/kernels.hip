@@ -550,114 +550,173 @@ __global__ __launch_bounds__(kThreads) void k_adam_persistent(MOEV_ADAM_TABLES, 
 // ------------------------------------------------------------------------------------
 // replay on low-precision state (Sec. 5.6 regimes): widen to FP32, the same FP32 step, narrow
 // ------------------------------------------------------------------------------------
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
-  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+// Per storage format: the register holding four consecutive elements, the element type of a
+// single (ragged tail) access, and the conversions of four values at a time.  The conversions
+// are the hardware's (round to nearest even; FP16 / BF16 overflow to infinity, NaN stays NaN);
+// the 8-bit ones do not saturate by themselves (overflow gives NaN / infinity), so the value
+// is clamped to the largest finite magnitude first, in a way that lets NaN through.
+template <uint32_t F> struct Fmt;
+
+// Keeps the compiler from folding the scale multiplication into the FP16 conversion next to it (a
+// mixed-precision fused multiply-add "x * s + 0": one rounding instead of two, and -0 becomes +0).
+__device__ __forceinline__ float opaque(float x) {
+  asm("" : "+v"(x));
+  return x;
 }
 
-// E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits; no infinities, S.1111.111 is NaN.
-__device__ __forceinline__ float e4m3_bits_to_float(uint32_t b) {
-  const uint32_t sign = (b & 0x80u) << 24, em = b & 0x7fu;
-  uint32_t bits;
-  if (em == 0x7fu) bits = 0x7fc00000u;
-  else if (em < 8u) bits = __float_as_uint(static_cast<float>(em) * 0x1p-9f);  // zero and subnormals: em * 2^-9, exact
-  else bits = (em << 20) + (120u << 23);                                        // exponent field + (127 - 7)
-  return __uint_as_float(bits | sign);
-}
-
-// Nearest value of an 8-bit format with MB mantissa bits and exponent bias BIAS, ties to even,
-// saturating at MAX_CODE (the largest finite magnitude); NaN -> NAN_CODE.
-template <int MB, int BIAS, uint32_t MAX_CODE, uint32_t NAN_CODE>
-__device__ __forceinline__ uint32_t fp8_bits(float x) {
-  const uint32_t u = __float_as_uint(x), a = u & 0x7fffffffu, sign = (u >> 24) & 0x80u;
-  if (a > 0x7f800000u) return sign | NAN_CODE;
-  constexpr int kShift = 23 - MB;
-  constexpr uint32_t kFirstNormal = static_cast<uint32_t>(127 - BIAS + 1) << 23;  // FP32 pattern of the smallest normal value
-  uint32_t code;
-  if (a >= kFirstNormal) {
-    // round the FP32 mantissa to MB bits (a carry runs into the exponent, as it should), re-bias
-    const uint32_t r = a + ((1u << (kShift - 1)) - 1u) + ((a >> kShift) & 1u);
-    code = (r >> kShift) - (static_cast<uint32_t>(127 - BIAS) << MB);
-    if (code > MAX_CODE) code = MAX_CODE;
-  } else {
-    // subnormal range: adding 2^(24 - BIAS - MB), whose last mantissa bit is worth the subnormal
-    // spacing 2^(1 - BIAS - MB), lets the FP32 adder do the rounding to nearest even
-    constexpr uint32_t kMagic = static_cast<uint32_t>(127 + 24 - BIAS - MB) << 23;
-    code = __float_as_uint(__uint_as_float(a) + __uint_as_float(kMagic)) - kMagic;
+template <> struct Fmt<kFmtF32> {
+  using Quad = u32x4;
+  using One = uint32_t;
+  static constexpr uint32_t kBytes = 4;
+  static __device__ __forceinline__ void widen(const Quad& q, float, float (&x)[4]) {
+    x[0] = __uint_as_float(q.x);
+    x[1] = __uint_as_float(q.y);
+    x[2] = __uint_as_float(q.z);
+    x[3] = __uint_as_float(q.w);
   }
-  return sign | code;
+  static __device__ __forceinline__ Quad narrow(const float (&x)[4], float) {
+    return Quad{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+  }
+};
+
+template <> struct Fmt<kFmtF16> {
+  using Quad = u32x2;
+  using One = uint16_t;
+  static constexpr uint32_t kBytes = 2;
+  static __device__ __forceinline__ void widen(const Quad& q, float inv, float (&x)[4]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t pair = h == 0 ? q.x : q.y;  // (a scalar copy: bit_cast straight from a vector element miscompiles)
+      const f32x2 w = __builtin_convertvector(__builtin_bit_cast(f16x2, pair), f32x2);
+      x[2 * h] = opaque(w.x) * inv;
+      x[2 * h + 1] = opaque(w.y) * inv;
+    }
+  }
+  static __device__ __forceinline__ Quad narrow(const float (&x)[4], float s) {
+    const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{opaque(x[0] * s), opaque(x[1] * s)}, f16x2));
+    const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{opaque(x[2] * s), opaque(x[3] * s)}, f16x2));
+    return Quad{lo, hi};
+  }
+};
+
+template <> struct Fmt<kFmtBF16> {
+  using Quad = u32x2;
+  using One = uint16_t;
+  static constexpr uint32_t kBytes = 2;
+  static __device__ __forceinline__ void widen(const Quad& q, float inv, float (&x)[4]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t pair = h == 0 ? q.x : q.y;
+      x[2 * h] = __uint_as_float(pair << 16) * inv;
+      x[2 * h + 1] = __uint_as_float(pair & 0xffff0000u) * inv;
+    }
+  }
+  static __device__ __forceinline__ Quad narrow(const float (&x)[4], float s) {
+    const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x[0] * s, x[1] * s}, bf16x2));
+    const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x[2] * s, x[3] * s}, bf16x2));
+    return Quad{lo, hi};
+  }
+};
+
+// clamp to [-limit, limit]; NaN passes (IEEE 754-2019 minimum / maximum propagate NaN)
+__device__ __forceinline__ float clamp_keep_nan(float x, float limit) {
+  return __builtin_elementwise_minimum(__builtin_elementwise_maximum(x, -limit), limit);
 }
 
-__device__ __forceinline__ uint32_t half_bits(float x) {
-  const uint32_t u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return ((u >> 16) & 0x8000u) | 0x7e00u;
-  return __builtin_bit_cast(uint16_t, static_cast<_Float16>(x));  // round to nearest even, overflow to infinity
-}
+template <> struct Fmt<kFmtE4M3> {   // 4 exponent bits (bias 7), 3 mantissa bits, no infinities, largest value 448
+  using Quad = uint32_t;
+  using One = uint8_t;
+  static constexpr uint32_t kBytes = 1;
+  static __device__ __forceinline__ void widen(const Quad& q, float inv, float (&x)[4]) {
+    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(q, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(q, true);
+    x[0] = lo.x * inv;
+    x[1] = lo.y * inv;
+    x[2] = hi.x * inv;
+    x[3] = hi.y * inv;
+  }
+  static __device__ __forceinline__ Quad narrow(const float (&x)[4], float s) {
+    int q = 0;
+    q = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_keep_nan(x[0] * s, 448.0f), clamp_keep_nan(x[1] * s, 448.0f), q, false);
+    q = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_keep_nan(x[2] * s, 448.0f), clamp_keep_nan(x[3] * s, 448.0f), q, true);
+    return static_cast<Quad>(q);
+  }
+};
 
-// W bytes per element; the format is uniform over the launch, so these branches do not diverge.
-template <uint32_t W>
-__device__ __forceinline__ float widen(uint32_t fmt, uint32_t bits, float inv_scale) {
-  if constexpr (W == 4) return __uint_as_float(bits);
-  else if constexpr (W == 2) return (fmt == kFmtBF16 ? __uint_as_float(bits << 16) : half_bits_to_float(bits)) * inv_scale;
-  else return (fmt == kFmtE5M2 ? half_bits_to_float(bits << 8) : e4m3_bits_to_float(bits)) * inv_scale;
-}
-template <uint32_t W>
-__device__ __forceinline__ uint32_t narrow(uint32_t fmt, float x, float scale) {
-  if constexpr (W == 4) return __float_as_uint(x);
-  else if constexpr (W == 2) return fmt == kFmtBF16 ? bf16_bits(x * scale) : half_bits(x * scale);
-  else return fmt == kFmtE5M2 ? fp8_bits<2, 15, 0x7bu, 0x7eu>(x * scale) : fp8_bits<3, 7, 0x7eu, 0x7fu>(x * scale);
-}
-
-// four consecutive elements of W bytes each
-template <uint32_t W> struct Quad;
-template <> struct Quad<4> { using type = u32x4; };
-template <> struct Quad<2> { using type = u32x2; };
-template <> struct Quad<1> { using type = uint32_t; };
-
-template <uint32_t W>
-__device__ __forceinline__ uint32_t quad_get(const typename Quad<W>::type& q, uint32_t e) {
-  if constexpr (W == 4) return q[e];
-  else if constexpr (W == 2) return (q[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-  else return (q >> (8 * e)) & 0xffu;
-}
-template <uint32_t W>
-__device__ __forceinline__ typename Quad<W>::type quad_make(const uint32_t (&c)[4]) {
-  if constexpr (W == 4) return u32x4{c[0], c[1], c[2], c[3]};
-  else if constexpr (W == 2) return u32x2{c[0] | (c[1] << 16), c[2] | (c[3] << 16)};
-  else return c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
-}
-template <uint32_t W> struct Single;
-template <> struct Single<4> { using type = uint32_t; };
-template <> struct Single<2> { using type = uint16_t; };
-template <> struct Single<1> { using type = uint8_t; };
+template <> struct Fmt<kFmtE5M2> {   // 5 exponent bits (bias 15), 2 mantissa bits, largest finite value 57344
+  using Quad = uint32_t;
+  using One = uint8_t;
+  static constexpr uint32_t kBytes = 1;
+  static __device__ __forceinline__ void widen(const Quad& q, float inv, float (&x)[4]) {
+    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_bf8(q, false), hi = __builtin_amdgcn_cvt_pk_f32_bf8(q, true);
+    x[0] = lo.x * inv;
+    x[1] = lo.y * inv;
+    x[2] = hi.x * inv;
+    x[3] = hi.y * inv;
+  }
+  static __device__ __forceinline__ Quad narrow(const float (&x)[4], float s) {
+    int q = 0;
+    q = __builtin_amdgcn_cvt_pk_bf8_f32(clamp_keep_nan(x[0] * s, 57344.0f), clamp_keep_nan(x[1] * s, 57344.0f), q, false);
+    q = __builtin_amdgcn_cvt_pk_bf8_f32(clamp_keep_nan(x[2] * s, 57344.0f), clamp_keep_nan(x[3] * s, 57344.0f), q, true);
+    return static_cast<Quad>(q);
+  }
+};
 
 struct LpScales {
   float s[4], inv[4];  // scale and its reciprocal (rounded once) of master, m, v, compute
 };
 
-// One element: codes in, codes out.  The compute weight is cast from the master weight as stored.
-template <uint32_t WP, uint32_t WM, uint32_t WV, uint32_t WC>
-__device__ __forceinline__ void adam_lp_element(uint32_t& p, uint32_t& m, uint32_t& v, uint32_t& cw, float g,
-                                                const uint32_t (&fmt)[4], const LpScales& sc, const AdamConst& c) {
-  float pf = widen<WP>(fmt[0], p, sc.inv[0]);
-  float mf = widen<WM>(fmt[1], m, sc.inv[1]);
-  float vf = widen<WV>(fmt[2], v, sc.inv[2]);
-  adam_element(pf, mf, vf, g, c);
-  p = narrow<WP>(fmt[0], pf, sc.s[0]);
-  m = narrow<WM>(fmt[1], mf, sc.s[1]);
-  v = narrow<WV>(fmt[2], vf, sc.s[2]);
-  cw = narrow<WC>(fmt[3], widen<WP>(fmt[0], p, sc.inv[0]), sc.s[3]);
+// Four elements: codes in, codes out.  The compute weights are cast from the master weights as stored.
+template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC>
+__device__ __forceinline__ void adam_lp_quad(typename Fmt<FP>::Quad& p, typename Fmt<FM>::Quad& m, typename Fmt<FV>::Quad& v,
+                                             typename Fmt<FC>::Quad& cw, const f32x4& g, const LpScales& sc,
+                                             const AdamConst& c) {
+  float pf[4], mf[4], vf[4];
+  Fmt<FP>::widen(p, sc.inv[0], pf);
+  Fmt<FM>::widen(m, sc.inv[1], mf);
+  Fmt<FV>::widen(v, sc.inv[2], vf);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) adam_element(pf[e], mf[e], vf[e], g[e], c);
+  p = Fmt<FP>::narrow(pf, sc.s[0]);
+  m = Fmt<FM>::narrow(mf, sc.s[1]);
+  v = Fmt<FV>::narrow(vf, sc.s[2]);
+  float stored[4];
+  Fmt<FP>::widen(p, sc.inv[0], stored);
+  cw = Fmt<FC>::narrow(stored, sc.s[3]);
+}
+
+// a quad whose first element is the single value at `ptr` (ragged tails)
+template <uint32_t F>
+__device__ __forceinline__ typename Fmt<F>::Quad quad_of_one(const uint8_t* base, uint64_t e) {
+  using One = typename Fmt<F>::One;
+  typename Fmt<F>::Quad q{};
+  const uint32_t bits = ld<false>(reinterpret_cast<const One*>(base) + e);
+  if constexpr (Fmt<F>::kBytes == 1) q = bits;
+  else q.x = bits;
+  return q;
+}
+template <uint32_t F>
+__device__ __forceinline__ void store_first(uint8_t* base, uint64_t e, const typename Fmt<F>::Quad& q) {
+  using One = typename Fmt<F>::One;
+  uint32_t bits;
+  if constexpr (Fmt<F>::kBytes == 1) bits = q;
+  else bits = q.x;
+  st<false>(reinterpret_cast<One*>(base) + e, static_cast<One>(bits));
 }
 
 // Elements [begin, end) of one tensor, in place; begin is a multiple of four.
-template <uint32_t WP, uint32_t WM, uint32_t WV, uint32_t WC, uint32_t T, uint32_t U, bool NT>
+template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC, uint32_t T, uint32_t U, bool NT>
 __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V, const float* __restrict__ G,
-                                              uint8_t* __restrict__ C, uint64_t begin, uint64_t end,
-                                              const uint32_t (&fmt)[4], const LpScales& sc, const AdamConst& c) {
-  using QP = typename Quad<WP>::type;
-  using QM = typename Quad<WM>::type;
-  using QV = typename Quad<WV>::type;
-  using QC = typename Quad<WC>::type;
+                                              uint8_t* __restrict__ C, uint64_t begin, uint64_t end, const LpScales& sc,
+                                              const AdamConst& c) {
+  using QP = typename Fmt<FP>::Quad;
+  using QM = typename Fmt<FM>::Quad;
+  using QV = typename Fmt<FV>::Quad;
+  using QC = typename Fmt<FC>::Quad;
+  constexpr uint32_t WP = Fmt<FP>::kBytes, WM = Fmt<FM>::kBytes, WV = Fmt<FV>::kBytes, WC = Fmt<FC>::kBytes;
   for (uint64_t base = begin + 4ull * threadIdx.x; base < end; base += 4ull * T * U) {
     QP p[U];
     QM m[U];
@@ -677,32 +736,26 @@ __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V
     for (uint32_t u = 0; u < U; ++u) {
       const uint64_t i = base + 4ull * T * u;
       if (i + 4 <= end) {
-        uint32_t pc[4], mc[4], vc[4], cc[4];
-#pragma unroll
-        for (uint32_t e = 0; e < 4; ++e) {
-          pc[e] = quad_get<WP>(p[u], e);
-          mc[e] = quad_get<WM>(m[u], e);
-          vc[e] = quad_get<WV>(v[u], e);
-          adam_lp_element<WP, WM, WV, WC>(pc[e], mc[e], vc[e], cc[e], g[u][e], fmt, sc, c);
-        }
-        st<NT>(reinterpret_cast<QP*>(P + i * WP), quad_make<WP>(pc));
-        st<NT>(reinterpret_cast<QM*>(M + i * WM), quad_make<WM>(mc));
-        st<NT>(reinterpret_cast<QV*>(V + i * WV), quad_make<WV>(vc));
-        st<NT>(reinterpret_cast<QC*>(C + i * WC), quad_make<WC>(cc));
+        QC cw;
+        adam_lp_quad<FP, FM, FV, FC>(p[u], m[u], v[u], cw, g[u], sc, c);
+        st<NT>(reinterpret_cast<QP*>(P + i * WP), p[u]);
+        st<NT>(reinterpret_cast<QM*>(M + i * WM), m[u]);
+        st<NT>(reinterpret_cast<QV*>(V + i * WV), v[u]);
+        st<NT>(reinterpret_cast<QC*>(C + i * WC), cw);
       } else if (i < end) {
-        // ragged tail of a tensor whose length is not a multiple of four
-        using SP = typename Single<WP>::type;
-        using SM = typename Single<WM>::type;
-        using SV = typename Single<WV>::type;
-        using SC = typename Single<WC>::type;
+        // ragged tail of a tensor whose length is not a multiple of four: one element at a time,
+        // in the first position of a quad
         for (uint64_t e = i; e < end; ++e) {
-          uint32_t pc = ld<false>(reinterpret_cast<const SP*>(P) + e), mc = ld<false>(reinterpret_cast<const SM*>(M) + e),
-                   vc = ld<false>(reinterpret_cast<const SV*>(V) + e), cc;
-          adam_lp_element<WP, WM, WV, WC>(pc, mc, vc, cc, ld<false>(G + e), fmt, sc, c);
-          st<false>(reinterpret_cast<SP*>(P) + e, static_cast<SP>(pc));
-          st<false>(reinterpret_cast<SM*>(M) + e, static_cast<SM>(mc));
-          st<false>(reinterpret_cast<SV*>(V) + e, static_cast<SV>(vc));
-          st<false>(reinterpret_cast<SC*>(C) + e, static_cast<SC>(cc));
+          QP p1 = quad_of_one<FP>(P, e);
+          QM m1 = quad_of_one<FM>(M, e);
+          QV v1 = quad_of_one<FV>(V, e);
+          QC c1;
+          const f32x4 g1 = {ld<false>(G + e), 0.0f, 0.0f, 0.0f};
+          adam_lp_quad<FP, FM, FV, FC>(p1, m1, v1, c1, g1, sc, c);
+          store_first<FP>(P, e, p1);
+          store_first<FM>(M, e, m1);
+          store_first<FV>(V, e, v1);
+          store_first<FC>(C, e, c1);
         }
       }
     }
@@ -710,7 +763,7 @@ __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V
 }
 
 // one tile per workgroup over the compacted tile list written by k_active_scan
-template <uint32_t WP, uint32_t WM, uint32_t WV, uint32_t WC, uint32_t T, uint32_t U, bool NT>
+template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC, uint32_t T, uint32_t U, bool NT>
 __global__ __launch_bounds__(T) void k_adam_lp(MOEV_ADAM_TABLES, const float* __restrict__ scales, const AdamArgs a) {
   const uint32_t tile = tile_of_workgroup(blockIdx.x, tile_start[a.n_tensors], a.xcd_regions);
   if (tile == ~0u) return;
@@ -726,12 +779,11 @@ __global__ __launch_bounds__(T) void k_adam_lp(MOEV_ADAM_TABLES, const float* __
     sc.s[k] = scales ? scales[static_cast<uint64_t>(k) * a.n_tensors + t] : 1.0f;
     sc.inv[k] = 1.0f / sc.s[k];
   }
-  const uint32_t fmt[4] = {a.fmt[0], a.fmt[1], a.fmt[2], a.fmt[3]};
-  adam_lp_range<WP, WM, WV, WC, T, U, NT>(static_cast<uint8_t*>(ptrs[t]),
+  adam_lp_range<FP, FM, FV, FC, T, U, NT>(static_cast<uint8_t*>(ptrs[t]),
                                           static_cast<uint8_t*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]),
                                           static_cast<uint8_t*>(ptrs[2ull * a.n_tensors + t]),
                                           static_cast<const float*>(grads[t]),
-                                          static_cast<uint8_t*>(ptrs[3ull * a.n_tensors + t]), begin, end, fmt, sc,
+                                          static_cast<uint8_t*>(ptrs[3ull * a.n_tensors + t]), begin, end, sc,
                                           adam_const(a));
 }
 
@@ -833,53 +885,66 @@ hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t thread
 }
 #undef MOEV_LAUNCH_ARGS
 
-// ---- replay on low-precision state: dispatch over width combinations and launch shapes ----
+// ---- replay on low-precision state: dispatch over format combinations and launch shapes ----
 bool lp_shape_supported(uint32_t threads, uint32_t unroll) {
-  return (threads == 64 || threads == 128 || threads == 256) && (unroll == 1 || unroll == 2 || unroll == 4);
-}
-
-bool lp_widths_supported(const uint8_t w[4]) {
-  const uint32_t key = w[0] * 1000u + w[1] * 100u + w[2] * 10u + w[3];
-  return key == 4442 || key == 2222 || key == 4441 || key == 2441 || key == 2121 || key == 1121;
+  return (threads == 64 || threads == 128 || threads == 256) && (unroll == 1 || unroll == 2);
 }
 
 namespace {
 
-template <uint32_t WP, uint32_t WM, uint32_t WV, uint32_t WC>
-hipError_t launch_adam_lp_widths(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
-                                 hipStream_t s) {
+constexpr uint32_t lp_key(uint32_t p, uint32_t m, uint32_t v, uint32_t c) { return ((p * 8 + m) * 8 + v) * 8 + c; }
+
+template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC>
+hipError_t launch_adam_lp_formats(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
+                                  hipStream_t s) {
 #define MOEV_LP_CASE(TT, UU)                                                                                         \
   if (threads == TT && unroll == UU) {                                                                               \
-    if (nt) hipLaunchKernelGGL((k_adam_lp<WP, WM, WV, WC, TT, UU, true>), dim3(blocks), dim3(TT), 0, s, a.tile_start, a.numel, \
+    if (nt) hipLaunchKernelGGL((k_adam_lp<FP, FM, FV, FC, TT, UU, true>), dim3(blocks), dim3(TT), 0, s, a.tile_start, a.numel, \
                                a.op_of_tensor, a.mask, a.ptrs, a.grads, a.scales, a);                                \
-    else hipLaunchKernelGGL((k_adam_lp<WP, WM, WV, WC, TT, UU, false>), dim3(blocks), dim3(TT), 0, s, a.tile_start, a.numel,   \
+    else hipLaunchKernelGGL((k_adam_lp<FP, FM, FV, FC, TT, UU, false>), dim3(blocks), dim3(TT), 0, s, a.tile_start, a.numel,   \
                             a.op_of_tensor, a.mask, a.ptrs, a.grads, a.scales, a);                                   \
     return hipGetLastError();                                                                                        \
   }
   MOEV_LP_CASE(64, 1)
   MOEV_LP_CASE(64, 2)
-  MOEV_LP_CASE(64, 4)
   MOEV_LP_CASE(128, 1)
   MOEV_LP_CASE(128, 2)
-  MOEV_LP_CASE(128, 4)
   MOEV_LP_CASE(256, 1)
   MOEV_LP_CASE(256, 2)
-  MOEV_LP_CASE(256, 4)
 #undef MOEV_LP_CASE
   return hipErrorInvalidValue;
 }
 
+// the format combinations (master, m, v, compute) that have a kernel
+#define MOEV_LP_COMBOS(X)                         \
+  X(kFmtF32, kFmtF32, kFmtF32, kFmtF16)           \
+  X(kFmtF16, kFmtF16, kFmtF16, kFmtF16)           \
+  X(kFmtF16, kFmtF16, kFmtF16, kFmtBF16)          \
+  X(kFmtF32, kFmtF32, kFmtF32, kFmtE4M3)          \
+  X(kFmtF16, kFmtF32, kFmtF32, kFmtE4M3)          \
+  X(kFmtF16, kFmtE4M3, kFmtF16, kFmtE4M3)         \
+  X(kFmtE4M3, kFmtE4M3, kFmtF16, kFmtE4M3)        \
+  X(kFmtBF16, kFmtBF16, kFmtBF16, kFmtBF16)       \
+  X(kFmtF16, kFmtE5M2, kFmtF16, kFmtE5M2)         \
+  X(kFmtE5M2, kFmtE4M3, kFmtBF16, kFmtE5M2)
+
 }  // namespace
 
-hipError_t launch_adam_lp(const AdamArgs& a, const uint8_t w[4], uint32_t blocks, uint32_t threads, uint32_t unroll,
-                          bool nt, hipStream_t s) {
-  switch (w[0] * 1000u + w[1] * 100u + w[2] * 10u + w[3]) {
-    case 4442: return launch_adam_lp_widths<4, 4, 4, 2>(a, blocks, threads, unroll, nt, s);
-    case 2222: return launch_adam_lp_widths<2, 2, 2, 2>(a, blocks, threads, unroll, nt, s);
-    case 4441: return launch_adam_lp_widths<4, 4, 4, 1>(a, blocks, threads, unroll, nt, s);
-    case 2441: return launch_adam_lp_widths<2, 4, 4, 1>(a, blocks, threads, unroll, nt, s);
-    case 2121: return launch_adam_lp_widths<2, 1, 2, 1>(a, blocks, threads, unroll, nt, s);
-    case 1121: return launch_adam_lp_widths<1, 1, 2, 1>(a, blocks, threads, unroll, nt, s);
+bool lp_formats_supported(const uint8_t f[4]) {
+  switch (lp_key(f[0], f[1], f[2], f[3])) {
+#define MOEV_LP_X(P, M, V, C) case lp_key(P, M, V, C):
+    MOEV_LP_COMBOS(MOEV_LP_X)
+#undef MOEV_LP_X
+    return true;
+    default: return false;
+  }
+}
+
+hipError_t launch_adam_lp(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt, hipStream_t s) {
+  switch (lp_key(a.fmt[0], a.fmt[1], a.fmt[2], a.fmt[3])) {
+#define MOEV_LP_X(P, M, V, C) case lp_key(P, M, V, C): return launch_adam_lp_formats<P, M, V, C>(a, blocks, threads, unroll, nt, s);
+    MOEV_LP_COMBOS(MOEV_LP_X)
+#undef MOEV_LP_X
     default: return hipErrorInvalidValue;
   }
 }

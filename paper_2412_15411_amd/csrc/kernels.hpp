@@ -83,12 +83,11 @@ hipError_t launch_adam_direct(const AdamArgs& a, uint32_t blocks, uint32_t threa
 hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,
                              hipStream_t s);
 
-// Replay on state stored in narrow formats: `width` = bytes per element of master, m, v, compute.
-// Same tile list and grid as launch_adam_direct (tile = threads * 4 elements * unroll).
-bool lp_widths_supported(const uint8_t width[4]);
+// Replay on state stored in other formats than FP32 / FP32 / FP32 / BF16: a.fmt = kFmt* of master, m, v,
+// compute.  Same tile list and grid as launch_adam_direct (tile = threads * 4 elements * unroll).
+bool lp_formats_supported(const uint8_t fmt[4]);
 bool lp_shape_supported(uint32_t threads, uint32_t unroll);
-hipError_t launch_adam_lp(const AdamArgs& a, const uint8_t width[4], uint32_t blocks, uint32_t threads, uint32_t unroll,
-                          bool nt, hipStream_t s);
+hipError_t launch_adam_lp(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt, hipStream_t s);
 
 // fixed grid of 256-thread workgroups walking the tile list
 hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);

@@ -22,6 +22,7 @@ REGIMES = dict(W.LOW_PRECISION_REGIMES)
 # (the precision the paper's own runs use for compute weights)
 VARIANTS = dict(REGIMES)
 VARIANTS["bf16_everywhere"] = (torch.bfloat16,) * 4
+VARIANTS["fp16_state_bf16_compute"] = (torch.float16, torch.float16, torch.float16, torch.bfloat16)
 VARIANTS["fp32_state_fp16_compute"] = (torch.float32, torch.float32, torch.float32, torch.float16)
 VARIANTS["e5m2_m_and_compute"] = (torch.float16, torch.float8_e5m2, torch.float16, torch.float8_e5m2)
 VARIANTS["e5m2_master"] = (torch.float8_e5m2, torch.float8_e4m3fn, torch.bfloat16, torch.float8_e5m2)
@@ -121,7 +122,7 @@ def test_low_precision_replay_matches_oracle(orc, dev, name):
                 assert after.kinds()[kind][t].tobytes() == start.kinds()[kind][t].tobytes()
 
 
-@pytest.mark.parametrize("shape", [(64, 2), (64, 4), (128, 1), (128, 4), (256, 1), (256, 2), (256, 4)])
+@pytest.mark.parametrize("shape", [(64, 2), (128, 1), (128, 2), (256, 1), (256, 2)])
 def test_low_precision_replay_launch_shapes(orc, dev, shape):
     dtypes = REGIMES["fp8_fp8_fp8+fp16"]
     wl = ragged_workload(77, max_numel=30000)
@@ -201,6 +202,28 @@ def test_narrowing_conversions_on_crafted_values(orc, dev, name, fmt_bits):
     mask_np = np.ones(2, dtype=np.uint8)
     ds, ref, fmts = run_both(orc, dev, wl, dtypes, st_cpu, None, grads, mask_np, hp, 3, lp_plan(wl, dtypes))
     assert_states_match(orc, ds, ref, fmts)
+
+
+@pytest.mark.parametrize("name", ["fp8_fp16_fp8+fp16", "e5m2_m_and_compute", "fp16_fp16_fp16+fp16", "bf16_everywhere"])
+def test_non_finite_gradients_through_the_narrowing_conversions(orc, dev, name):
+    """NaN stays NaN in every format; infinities saturate in the 8-bit formats and stay infinite in the 16-bit
+    ones (beta1 = 0: m = narrow(g))."""
+    dtypes = VARIANTS[name]
+    inf = float("inf")
+    g = np.array([np.nan, -np.nan, inf, -inf, 3e38, -3e38, 500.0, -500.0, 6e4, -6e4, 7e4, 0.0, -0.0, 1.0] * 3, dtype=np.float32)
+    wl = W.Workload("probe", [(0, g.size)], [0], 1)
+    st_cpu = W.make_low_precision_state(wl, dtypes, [1.0, 1.0, 1.0, 1.0], seed=3)
+    hp = orc.AdamHP(lr=0.0, beta1=0.0, beta2=0.0)
+    ds, ref, fmts = run_both(orc, dev, wl, dtypes, st_cpu, None, [torch.from_numpy(g.copy())], np.ones(1, np.uint8), hp, 3,
+                             lp_plan(wl, dtypes))
+    assert_states_match(orc, ds, ref, fmts)
+    m = ds.to_oracle().m[0]
+    vals = [orc.decode(fmts[1], int(c)) for c in m[:14]]
+    assert np.isnan(vals[0]) and np.isnan(vals[1])
+    top = {orc.FMT_E4M3: 448.0, orc.FMT_E5M2: 57344.0}.get(fmts[1], inf)
+    assert vals[2] == top and vals[3] == -top
+    if fmts[1] != orc.FMT_BF16:   # 3e38 is beyond every format's range except bfloat16's
+        assert vals[4] == top and vals[5] == -top
 
 
 def test_fp8_compute_cast_of_fp32_master_on_crafted_values(orc, dev):
