@@ -591,6 +591,13 @@ int ckpt_plan(const moev_plan_cfg* cfg, moev_plan** out) {
       delete pl;
       return fail(MOEV_E_INVAL, "ckpt_plan: slot too large");
     }
+  // Replay launch shape: state stored in 6 bytes per parameter or fewer keeps too few bytes in flight with one
+  // 16-byte gradient access per lane; two accesses per lane and 128 threads measured best there.
+  const auto& h = pl->host;
+  if (!fp32_regime(h) && h.width[MOEV_KIND_MASTER] + h.width[MOEV_KIND_ADAM_M] + h.width[MOEV_KIND_ADAM_V] <= 6) {
+    pl->adam_threads = 128;
+    pl->adam_unroll = 2;
+  }
   compute_host_tiles(pl);
   *out = pl;
   return MOEV_OK;
