@@ -180,6 +180,52 @@ def test_fullsize_replay_sampled(orc, dev):
         _release()
 
 
+@pytest.mark.parametrize("regime", ["fp8_fp8_fp8+fp16", "fp16_fp16_fp16+fp16", "fp8_fp16_fp32+fp32"])
+def test_fullsize_low_precision_replay_sampled(orc, dev, regime):
+    """configs[1] at full size with the state stored as a Sec. 5.6 regime, in the launch configuration
+    `bench.py --regime` times: sampled windows of every tensor against the oracle's low-precision step,
+    code for code; frozen tensors keep their bits."""
+    from helpers import ORACLE_FMT_OF_DTYPE
+    lib_fmt = {torch.float32: B.FMT_F32, torch.float16: B.FMT_F16, torch.bfloat16: B.FMT_BF16,
+               torch.float8_e4m3fn: B.FMT_E4M3, torch.float8_e5m2: B.FMT_E5M2}
+    wl, it_index = W.mixtral_layer(), 5
+    dtypes = W.LOW_PRECISION_REGIMES[regime]
+    fmts = tuple(ORACLE_FMT_OF_DTYPE[d] for d in dtypes)
+    hp = hp_of(wl)
+    per_kind = W.default_scales(dtypes)
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
+                       formats=[lib_fmt[d] for d in dtypes])
+    st = W.make_low_precision_state(wl, dtypes, per_kind, seed=3, device=dev)
+    state = B.State(*[st[k] for k in KINDS])
+    d_scales = torch.tensor([[x] * wl.n_tensors for x in per_kind], dtype=torch.float32, device=dev)
+    step = wl.t0 + it_index + 1
+    active = [1 if s <= it_index else 0 for s in wl.slot_of_op]
+    mask = torch.tensor(active, dtype=torch.uint8, device=dev)
+    full = W.make_grads(wl, step, seed=3, device=dev)
+    grads = [g if active[wl.tensors[t][0]] else None for t, g in enumerate(full)]
+    rng = np.random.default_rng(1)
+    before = {}
+    for t, (op, numel) in enumerate(wl.tensors):
+        wins = [(a // 4, b // 4) for a, b in sample_windows(numel * 4, rng, 4, 4096 * 4)]
+        before[t] = [(a, b, {k: st[k][t][a:b].clone() for k in KINDS}, full[t][a:b].clone()) for a, b in wins]
+    B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, step, mask, grads, state, d_scales=d_scales)
+    torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan)
+    checked = 0
+    for t, (op, numel) in enumerate(wl.tensors):
+        for a, b, old, g in before[t]:
+            now = {k: np_of(st[k][t][a:b]) for k in KINDS}
+            ref = {k: np_of(old[k]) for k in KINDS}
+            if active[op]:
+                orc.adam_tensor_lp(ref["master"], ref["m"], ref["v"], np_of(g), ref["compute"], hp, step, fmts, per_kind)
+            for k in KINDS:
+                assert now[k].tobytes() == ref[k].tobytes(), f"{regime} tensor {t} {k} window {a}"
+            checked += b - a
+    print(f"{regime}: {checked} sampled parameters match the oracle code for code")
+    del st, state, full, grads, before
+    _release()
+
+
 def test_fullsize_ep_rank_share_pack(orc, dev):
     """configs[3]: 180 GB of state resident in HBM, slot 0 (1,920 segments, 41.9 GB packed): sampled
     windows of every segment plus the word-sum property; then restore into the poisoned state."""
