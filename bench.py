@@ -615,6 +615,32 @@ def main():
                 "gemm_ms_alone": round(alone_ms, 2), "gemm_ms_with_drain": round(g0.elapsed_time(g1), 2)}
         del host
 
+    # ---- what the measured rates mean for the method's own model (Algorithm 1, Sec. 3.6, App. C) -----------
+    # Inputs that are MEASURED here: the host-link rate of the drain (B_PCIe), the time the state is held for
+    # a snapshot (the pack of the largest slot; the drain runs under the next iteration), the conversion time
+    # of a window.  Inputs that are ASSUMED: the iteration time (this bench trains nothing; the paper's runs
+    # imply 1-3 s) and the MTBF values of the paper's tables.  All formulas are the library's host helpers.
+    if "drain" in out:
+        per_op = wl.n_params / wl.n_ops
+        link = out["drain"]["GBs"] * 1e9
+        stall_s = max(e0.elapsed_time(e1) for kind, _, e0, e1 in timings if kind == "pack") / 1e3
+        convert_s = (out["fused_conversion"]["ms_per_window"] if "fused_conversion" in out else
+                     (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / args.steps) / 1e3
+        rows = []
+        for t_iter in (0.25, 0.5, 1.0, 2.0):
+            w, a = B.moev_find_window_size(wl.n_ops, t_iter, widths[3] * per_op, widths[0] * per_op,
+                                           (widths[1] + widths[2]) * per_op, link)
+            expected, worst = B.moev_recovery_time(True, w, t_iter)
+            rows.append({"t_iter_s": t_iter, "window": w, "active_per_slot": a,
+                         "expected_recovery_s": round(expected + convert_s, 3), "worst_recovery_s": round(worst + convert_s, 3),
+                         "ettr": {f"mtbf_{m}s": round(B.moev_ettr(stall_s, t_iter, 1.0, expected + convert_s, m), 4)
+                                  for m in (600, 1800, 3600)}})
+        out["what_if"] = {"assumed": "t_iter_s, mtbf", "measured": {"host_link_GBs": out["drain"]["GBs"],
+                          "snapshot_stall_s": round(stall_s, 5), "window_conversion_s": round(convert_s, 4)},
+                          "note": "FindWindowSize on this GPU's operators with the measured link rate; recovery = 1.5 W T_iter "
+                                  "(expected) / 2 W T_iter (worst) plus the measured conversion; ETTR with a snapshot every iteration",
+                          "rows": rows}
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.seed, args.regime)
 
