@@ -26,6 +26,13 @@
  *   - Streams and events are passed as void* (hipStream_t / hipEvent_t); NULL stream = the
  *     default stream.
  *   - There is no CPU fallback: GPU calls fail with MOEV_E_HIP when no device is usable.
+ *   - A plan may be used from several host threads (its calls are serialised by a mutex) and on
+ *     several streams.  Its device tables (layout, tile maps, the cached tables of state and
+ *     gradient pointers) are written on the stream of the call that (re)builds them; a later call
+ *     on another stream waits for that write.  The pointer tables are shared by all calls on a
+ *     plan: a call that passes DIFFERENT state or gradient pointers than the previous one rewrites
+ *     them, so it must not be enqueued while a kernel of that plan may still run on ANOTHER
+ *     stream (order the streams, or use one plan per concurrently processed state).
  *
  * Packed snapshot format (this library's definition; the paper copies per operator and
  * defines none).  Little endian.

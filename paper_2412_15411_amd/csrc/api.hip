@@ -116,6 +116,13 @@ struct moev_plan {
   StageSlot ring[kRing];
   int ring_next = 0;
   hipEvent_t tables_uploaded = nullptr;     // recorded after the copy out of pinned_tables
+  // Cross-stream ordering of the device tables: each table is written on the stream of the call that
+  // (re)builds it; a later call on another stream waits for that write before its kernel reads the table.
+  struct Written {
+    hipEvent_t event = nullptr;
+    hipStream_t stream = nullptr;
+    bool recorded = false;
+  } scan_done, state_written, grads_written;
   std::vector<uint32_t> slot_tiles, slot_tiles_unpack;  // host-side tile counts (grid sizing only)
   std::vector<uint32_t> slot_first_compute_tile;        // unpack tiles in front of the first compute segment
   uint64_t* d_src_off = nullptr;            // [window][3][n_tensors] snapshot offsets of master, m, v (~0: absent)
@@ -136,6 +143,8 @@ struct moev_plan {
         (void)hipEventSynchronize(tables_uploaded);
         (void)hipEventDestroy(tables_uploaded);
       }
+      for (Written* w : {&scan_done, &state_written, &grads_written})
+        if (w->event) (void)hipEventDestroy(w->event);
       if (d_tables) (void)hipFree(d_tables);
       if (d_state_ptrs) (void)hipFree(d_state_ptrs);
       if (d_grad_ptrs) (void)hipFree(d_grad_ptrs);
@@ -214,6 +223,8 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
     MOEV_HIP(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
   }
   MOEV_HIP(hipEventCreateWithFlags(&pl->tables_uploaded, hipEventDisableTiming));
+  for (moev_plan::Written* w : {&pl->scan_done, &pl->state_written, &pl->grads_written})
+    MOEV_HIP(hipEventCreateWithFlags(&w->event, hipEventDisableTiming));
   char* d = pl->d_tables;
   pl->d_segs = reinterpret_cast<moev::SegDesc*>(d + o_segs);
   pl->d_numel = reinterpret_cast<uint64_t*>(d + o_numel);
@@ -301,14 +312,24 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
   MOEV_HIP(hipMemcpyAsync(pl->d_tables, pl->pinned_tables, input_bytes, hipMemcpyHostToDevice, s));
   MOEV_HIP(hipEventRecord(pl->tables_uploaded, s));
   MOEV_HIP(moev::launch_layout_scan(pl->d_jobs, 2 * h.window + 1, s));
+  MOEV_HIP(hipEventRecord(pl->scan_done.event, s));
+  pl->scan_done.stream = s;
+  pl->scan_done.recorded = true;
   compute_host_tiles(pl);
   pl->uploaded = true;
   return MOEV_OK;
 }
 
+// Orders stream `s` after the writes of the device tables that happened on other streams.
+int wait_for_tables(moev_plan* pl, hipStream_t s) {
+  for (moev_plan::Written* w : {&pl->scan_done, &pl->state_written, &pl->grads_written})
+    if (w->recorded && w->stream != s) MOEV_HIP(hipStreamWaitEvent(s, w->event, 0));
+  return MOEV_OK;
+}
+
 // Makes the device copy of a pointer table current.  Unchanged tables cost one memcmp.
 int sync_ptr_table(moev_plan* pl, std::vector<void*>& cache, bool& valid, void** d_table,
-                   const std::vector<void*>& wanted, hipStream_t s) {
+                   const std::vector<void*>& wanted, hipStream_t s, moev_plan::Written& written) {
   if (valid && cache == wanted) return MOEV_OK;
   StageSlot& slot = pl->ring[pl->ring_next];
   pl->ring_next = (pl->ring_next + 1) % kRing;
@@ -317,6 +338,9 @@ int sync_ptr_table(moev_plan* pl, std::vector<void*>& cache, bool& valid, void**
   MOEV_HIP(hipMemcpyAsync(d_table, slot.pinned, wanted.size() * sizeof(void*), hipMemcpyHostToDevice, s));
   MOEV_HIP(hipEventRecord(slot.done, s));
   slot.in_flight = true;
+  MOEV_HIP(hipEventRecord(written.event, s));
+  written.stream = s;
+  written.recorded = true;
   cache = wanted;
   valid = true;
   return MOEV_OK;
@@ -338,7 +362,9 @@ int bind_state(moev_plan* pl, const moev_state* st, hipStream_t s) {
     wanted[2ull * n + t] = st->v[t];
     wanted[3ull * n + t] = st->compute[t];
   }
-  return sync_ptr_table(pl, pl->state_cache, pl->state_valid, pl->d_state_ptrs, wanted, s);
+  int rc = sync_ptr_table(pl, pl->state_cache, pl->state_valid, pl->d_state_ptrs, wanted, s, pl->state_written);
+  if (rc != MOEV_OK) return rc;
+  return wait_for_tables(pl, s);
 }
 
 uint32_t grid_for(const moev_plan* pl, uint32_t tiles, int64_t cap) {
@@ -498,7 +524,9 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   rc = bind_state(p, state, s);
   if (rc != MOEV_OK) return rc;
   std::vector<void*> g(grads, grads + h.n_tensors);
-  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s);
+  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s, p->grads_written);
+  if (rc != MOEV_OK) return rc;
+  rc = wait_for_tables(p, s);
   if (rc != MOEV_OK) return rc;
 
   moev::AdamArgs a{};
@@ -824,6 +852,8 @@ int ckpt_plan_device_layout(moev_plan* p, uint32_t slot, uint64_t* dst_off_out, 
   std::lock_guard<std::mutex> lock(p->mu);
   hipStream_t s = static_cast<hipStream_t>(stream);
   int rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = wait_for_tables(p, s);
   if (rc != MOEV_OK) return rc;
   const auto& sl = p->host.slots[slot];
   if (dst_off_out && sl.n_segments)

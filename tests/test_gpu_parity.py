@@ -357,6 +357,41 @@ def test_pack_drain_restore_roundtrip_through_pinned_host(orc, dev):
         side.synchronize()
 
 
+def test_fresh_plan_used_on_two_streams_without_host_synchronisation(orc, dev):
+    """The plan's device tables are built by its first call, on that call's stream; the next call runs on
+    another stream, ordered only by the caller's event on the data.  Pack on stream A, unpack (into another
+    state, so the pointer table is rewritten) and replay on stream B: results equal the oracle's."""
+    wl = ragged_workload(41, max_numel=300000)
+    model, hp = model_of(wl), hp_of(wl)
+    st_cpu = W.make_state(wl, seed=12)
+    truth = state_of(st_cpu)
+    grads_cpu = W.make_grads(wl, 11, seed=12)
+    for k in (0, wl.window - 1):
+        plan = make_plan(wl)                      # fresh: nothing uploaded yet
+        src, dst = DeviceState(st_cpu, dev), DeviceState(st_cpu, dev)
+        dst.poison()
+        ref = dst.to_oracle()
+        buf = packed_buffer(plan, dev, k)
+        mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+        grads = [g.to(dev) for g in grads_cpu]
+        a, b = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        packed_ready = torch.cuda.Event()
+        B.snapshot_pack(plan, k, 10, src.state, buf, stream=a)
+        packed_ready.record(a)
+        b.wait_event(packed_ready)
+        B.restore_unpack(plan, k, None, buf, dst.state, mask, stream=b)
+        B.convert_replay(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, 11, mask,
+                         [g if wl.slot_of_op[wl.tensors[t][0]] == k else None for t, g in enumerate(grads)], dst.state, stream=b)
+        torch.cuda.synchronize()
+        B.ckpt_plan_device_status(plan)
+        ref_mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        orc.unpack(model, k, orc.pack(model, k, 10, truth), ref, ref_mask)
+        orc.replay_step(model, hp, 11, ref_mask, [g.numpy() for g in grads_cpu], ref)
+        assert states_equal(dst.to_oracle(), ref) == [] and dst.guards_intact()
+        assert np.array_equal(mask.cpu().numpy(), ref_mask)
+
+
 def test_foreign_snapshots_are_refused(orc, dev):
     """Host path: MISMATCH before anything is enqueued.  Device path: the kernel skips the scatter
     and raises the status word; the state stays as it was."""
