@@ -615,6 +615,34 @@ def main():
                 "gemm_ms_alone": round(alone_ms, 2), "gemm_ms_with_drain": round(g0.elapsed_time(g1), 2)}
         del host
 
+    # ---- upstream logging (Sec. 3.4): boundary tensors into the pinned ring and back, host link --------------
+    if not args.no_drain:
+        entry_bytes, n_entries = 256 << 20, 8        # a [32 x 2048 x 2048] 2-byte activation; 8 micro-batches
+        ring = torch.empty(n_entries * entry_bytes, dtype=torch.uint8).pin_memory()
+        log_ring = B.uplog_create(ring, max_entries=64)
+        acts = torch.empty(entry_bytes, dtype=torch.uint8, device=dev).fill_(7)
+        back = torch.empty_like(acts)
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(side)
+        for mb in range(n_entries):
+            with torch.cuda.stream(side):
+                acts.fill_(mb + 1)                   # every entry differs (stream-ordered with the copies)
+            B.uplog_append(log_ring, wl.t0, mb, B.ACTIVATION, acts, side_stream=side)
+        e1.record(side)
+        for mb in range(n_entries):
+            B.uplog_replay(log_ring, wl.t0, mb, B.ACTIVATION, back, stream=side)
+        e2.record(side)
+        side.synchronize()
+        live = B.uplog_stats(log_ring)[0]
+        dropped = B.uplog_gc(log_ring, wl.t0 + 1)
+        out["upstream_log"] = {"bound": "host-link", "entries": n_entries, "entry_bytes": entry_bytes,
+                               "append_GBs": round(n_entries * entry_bytes / (e0.elapsed_time(e1) / 1e3) / 1e9, 2),
+                               "replay_GBs": round(n_entries * entry_bytes / (e1.elapsed_time(e2) / 1e3) / 1e9, 2),
+                               "round_trip_ok": bool((back == n_entries).all().item()) and live == n_entries and dropped == n_entries}
+        del ring, log_ring, acts, back
+
     # ---- what the measured rates mean for the method's own model (Algorithm 1, Sec. 3.6, App. C) -----------
     # Inputs that are MEASURED here: the host-link rate of the drain (B_PCIe), the time the state is held for
     # a snapshot (the pack of the largest slot; the drain runs under the next iteration), the conversion time
