@@ -33,6 +33,12 @@
  *     plan: a call that passes DIFFERENT state or gradient pointers than the previous one rewrites
  *     them, so it must not be enqueued while a kernel of that plan may still run on ANOTHER
  *     stream (order the streams, or use one plan per concurrently processed state).
+ *   - HIP graphs: a call whose tables are resident (same plan settings, same state and gradient
+ *     pointers as an earlier call) enqueues kernels only and may be captured into a graph; pass
+ *     every gradient pointer in every iteration (frozen operators' entries are not read) so that
+ *     the table does not change.  A call that would have to build or upload a table while its
+ *     stream is capturing fails with MOEV_E_INVAL and records nothing.  Calls given a pinned host
+ *     snapshot (h_pinned) record a host-to-device copy node.
  *
  * Packed snapshot format (this library's definition; the paper copies per operator and
  * defines none).  Little endian.

@@ -263,6 +263,17 @@ int allocate_device_side(moev_plan* pl, int dev, hipStream_t s) {
   return MOEV_OK;
 }
 
+// Table uploads allocate, copy out of reused pinned staging and wait on events: none of that may be
+// recorded into a HIP graph.  Calls whose tables are already resident enqueue kernels only.
+int refuse_under_capture(hipStream_t s, const char* what) {
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  MOEV_HIP(hipStreamIsCapturing(s, &status));
+  if (status != hipStreamCaptureStatusNone)
+    return fail(MOEV_E_INVAL, "%s while the stream is being captured into a graph: make one call with the same plan "
+                "settings and the same state / gradient pointers before the capture", what);
+  return MOEV_OK;
+}
+
 // Uploads the static tables and runs the on-device layout scan.  Caller holds pl->mu.
 int upload_locked(moev_plan* pl, hipStream_t s) {
   const auto& h = pl->host;
@@ -272,6 +283,10 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
   if (pl->device >= 0 && pl->device != dev)
     return fail(MOEV_E_INVAL, "plan lives on device %d but device %d is current", pl->device, dev);
   if (pl->uploaded) return MOEV_OK;
+  {
+    int rc = refuse_under_capture(s, "the plan's device tables would have to be built");
+    if (rc != MOEV_OK) return rc;
+  }
 
   if (pl->device < 0) {
     int rc = allocate_device_side(pl, dev, s);
@@ -322,8 +337,14 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
 
 // Orders stream `s` after the writes of the device tables that happened on other streams.
 int wait_for_tables(moev_plan* pl, hipStream_t s) {
-  for (moev_plan::Written* w : {&pl->scan_done, &pl->state_written, &pl->grads_written})
-    if (w->recorded && w->stream != s) MOEV_HIP(hipStreamWaitEvent(s, w->event, 0));
+  for (moev_plan::Written* w : {&pl->scan_done, &pl->state_written, &pl->grads_written}) {
+    if (!w->recorded || w->stream == s) continue;
+    if (hipEventQuery(w->event) == hipSuccess) {  // long finished: nothing to order, now or later
+      w->recorded = false;
+      continue;
+    }
+    MOEV_HIP(hipStreamWaitEvent(s, w->event, 0));
+  }
   return MOEV_OK;
 }
 
@@ -331,6 +352,10 @@ int wait_for_tables(moev_plan* pl, hipStream_t s) {
 int sync_ptr_table(moev_plan* pl, std::vector<void*>& cache, bool& valid, void** d_table,
                    const std::vector<void*>& wanted, hipStream_t s, moev_plan::Written& written) {
   if (valid && cache == wanted) return MOEV_OK;
+  {
+    int rc = refuse_under_capture(s, "a table of state or gradient pointers would have to be uploaded");
+    if (rc != MOEV_OK) return rc;
+  }
   StageSlot& slot = pl->ring[pl->ring_next];
   pl->ring_next = (pl->ring_next + 1) % kRing;
   if (slot.in_flight) MOEV_HIP(hipEventSynchronize(slot.done));

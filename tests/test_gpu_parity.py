@@ -392,6 +392,69 @@ def test_fresh_plan_used_on_two_streams_without_host_synchronisation(orc, dev):
         assert np.array_equal(mask.cpu().numpy(), ref_mask)
 
 
+def test_conversion_window_captured_in_a_graph(orc, dev):
+    """Launch-bound windows (configs[0]) can be replayed from a HIP graph: with resident tables the calls
+    enqueue kernels only.  The graph is replayed several times with eager work and synchronisations in
+    between, and every replay must reproduce the eager conversion; a call that would have to upload a table
+    during capture is refused and records nothing."""
+    wl = W.tiny_moe()
+    hp = hp_of(wl)
+    st_cpu = W.make_state(wl, seed=5)
+    plan = make_plan(wl)
+    live = DeviceState(st_cpu, dev)
+    everyone = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    per_iter = {t: [g.to(dev) for g in W.make_grads(wl, t, seed=5)] for t in range(wl.t0 + 1, wl.t0 + wl.window + 1)}
+    gbuf = [torch.empty_like(g) for g in per_iter[wl.t0 + 1]]     # persistent gradient buffers: constant pointers
+    bufs = []
+    for k in range(wl.window):
+        bufs.append(packed_buffer(plan, dev, k))
+        B.snapshot_pack(plan, k, wl.t0 + k, live.state, bufs[k])
+        B.convert_replay(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, wl.t0 + k + 1, everyone,
+                         per_iter[wl.t0 + k + 1], live.state)
+    torch.cuda.synchronize()
+    rebuilt = DeviceState(st_cpu, dev)
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+
+    def window():
+        mask.zero_()
+        for i in range(wl.window):
+            for dst, src in zip(gbuf, per_iter[wl.t0 + i + 1]):
+                dst.copy_(src)
+            B.restore_unpack(plan, i, None, bufs[i], rebuilt.state, mask, stream=torch.cuda.current_stream())
+            B.convert_replay(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, wl.t0 + i + 1, mask, gbuf,
+                             rebuilt.state, stream=torch.cuda.current_stream())
+
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        rebuilt.poison()
+        window()                                   # eager: also makes the plan's tables resident
+        s.synchronize()
+        eager = rebuilt.to_oracle()
+        assert states_equal(eager, live.to_oracle()) == []
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            window()
+        for rep in range(3):
+            rebuilt.poison()                       # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert states_equal(rebuilt.to_oracle(), eager) == [], f"replay {rep}"
+            assert bool(mask.cpu().all()) and rebuilt.guards_intact()
+        B.ckpt_plan_device_status(plan, s)
+        # another state (other pointers) inside a capture: refused, nothing recorded, the capture stays valid
+        other = DeviceState(st_cpu, dev)
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2, stream=s):
+            with pytest.raises(B.MoevError) as e:
+                B.restore_unpack(plan, 0, None, bufs[0], other.state, mask, stream=torch.cuda.current_stream())
+            assert e.value.code == B.E_INVAL
+            mask.zero_()
+        g2.replay()
+        torch.cuda.synchronize()
+        assert states_equal(other.to_oracle(), state_of(st_cpu)) == []
+
+
 def test_foreign_snapshots_are_refused(orc, dev):
     """Host path: MISMATCH before anything is enqueued.  Device path: the kernel skips the scatter
     and raises the status word; the state stays as it was."""
