@@ -128,8 +128,8 @@ def cpu_baseline(cfg_name, seed, regime="fp32"):
 
     oracle.build()
     if cfg_name == "c1" and regime != "fp32":   # the oracle converts element by element there: a smaller sample
-        wl = W.mixtral_layer(d_ff=14336 // 32)
-        sample = "configs[1] with d_ff 448 (1/32 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
+        wl = W.mixtral_layer(d_ff=14336 // 64)
+        sample = "configs[1] with d_ff 224 (1/64 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
     elif cfg_name == "c1":
         wl = W.mixtral_layer(d_ff=14336 // 8)
         sample = "configs[1] with d_ff 1792 (1/8 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
