@@ -91,6 +91,59 @@ int main(void) {
   for (int e = 0; e < N_OPS; ++e)
     if (mask[e] != 1) return printf("operator %d not active\n", e), 6;
   ckpt_plan_free(plan);
+
+  /* The same operators with the state stored in a low-precision regime (Sec. 5.6): 8-bit master weights,
+   * 8-bit first and 16-bit second moments, 8-bit compute weights, one scale per tensor and kind.  With zero
+   * gradients and zero first moments the step leaves the stored master weights alone and casts the compute
+   * weights from them (same format, same scale: the same codes). */
+  memset(&cfg, 0, sizeof cfg);
+  cfg.n_ops = N_OPS;
+  cfg.n_tensors = N_TENSORS;
+  cfg.tensors = tensors;
+  cfg.mode = MOEV_EXPLICIT;
+  cfg.window = 2;
+  cfg.slot_of_op = slots;
+  cfg.master_fmt = MOEV_FMT_E4M3;
+  cfg.m_fmt = MOEV_FMT_E4M3;
+  cfg.v_fmt = MOEV_FMT_F16;
+  cfg.compute_fmt = MOEV_FMT_E4M3;
+  CHECK_MOEV(ckpt_plan(&cfg, &plan));
+  if (ckpt_plan_width(plan, MOEV_KIND_MASTER) != 1 || ckpt_plan_width(plan, MOEV_KIND_ADAM_V) != 2) return printf("bad widths\n"), 7;
+  uint8_t* h_codes[N_TENSORS];
+  for (int t = 0; t < N_TENSORS; ++t) {
+    size_t n = numel[t];
+    h_codes[t] = (uint8_t*)malloc(n);
+    for (size_t i = 0; i < n; ++i) {
+      uint8_t code = (uint8_t)((i * 13 + (size_t)t) & 0xff);
+      if ((code & 0x7f) == 0x7f || (code & 0x7f) == 0) code = 0x38;   /* no NaN, no zero (a zero keeps its value, not its sign) */
+      h_codes[t][i] = code;
+    }
+    CHECK_HIP(hipMemcpy(master[t], h_codes[t], n, hipMemcpyHostToDevice));   /* the FP32-sized allocations are large enough */
+    CHECK_HIP(hipMemset(m[t], 0, n));
+    CHECK_HIP(hipMemset(v[t], 0x3c, n * 2));    /* 0x3c3c: a positive FP16 value */
+    CHECK_HIP(hipMemset(c[t], 0, n));
+  }
+  float h_scales[4 * N_TENSORS], *d_scales;
+  for (int k = 0; k < 4; ++k)
+    for (int t = 0; t < N_TENSORS; ++t) h_scales[k * N_TENSORS + t] = (k == 0 || k == 3) ? 1024.0f : 4096.0f;
+  CHECK_HIP(hipMalloc((void**)&d_scales, sizeof h_scales));
+  CHECK_HIP(hipMemcpy(d_scales, h_scales, sizeof h_scales, hipMemcpyHostToDevice));
+  uint8_t ones[N_OPS] = {1, 1, 1, 1};
+  CHECK_HIP(hipMemcpy(d_mask, ones, N_OPS, hipMemcpyHostToDevice));
+  moev_adam lp = {1e-3f, 0.9f, 0.95f, 1e-8f, 0.0f, 12, NULL};
+  lp.d_scales = d_scales;
+  CHECK_MOEV(convert_replay(plan, &lp, d_mask, g, &st, main_s));
+  CHECK_HIP(hipStreamSynchronize(main_s));
+  CHECK_MOEV(ckpt_plan_device_status(plan, main_s));
+  for (int t = 0; t < N_TENSORS; ++t) {
+    uint8_t* back = (uint8_t*)malloc(numel[t]);
+    CHECK_HIP(hipMemcpy(back, master[t], numel[t], hipMemcpyDeviceToHost));
+    if (memcmp(back, h_codes[t], numel[t]) != 0) return printf("low-precision master %d changed\n", t), 8;
+    CHECK_HIP(hipMemcpy(back, c[t], numel[t], hipMemcpyDeviceToHost));
+    if (memcmp(back, h_codes[t], numel[t]) != 0) return printf("low-precision compute %d is not the cast of the master weights\n", t), 9;
+    free(back);
+  }
+  ckpt_plan_free(plan);
   printf("ok\n");
   return 0;
 }
