@@ -174,7 +174,10 @@ enum {
   MOEV_TUNE_NONTEMPORAL = 4,     /* 1 = streaming (nontemporal) loads and stores, 0 = default caching */
   MOEV_TUNE_PERSISTENT = 5,      /* 0 = one tile per workgroup, 1 = fixed grid */
   MOEV_TUNE_COPY_THREADS = 6,    /* one tile per workgroup: threads (64..1024) and accesses per lane (1, 2, 4); */
-  MOEV_TUNE_COPY_UNROLL = 7,     /*   supported pairs: (64|128|256|512|1024, 1), (64|128|256|512, 2), (64|128|256, 4) */
+  MOEV_TUNE_COPY_UNROLL = 7,     /*   supported pairs: (64|128|256|512|1024, 1), (64|128|256|512, 2), (64|128|256, 4).
+                                      Until either is set the pack uses 256 threads and picks the accesses per lane
+                                      per slot: 2 where the slot gathers compute-weight segments averaging under
+                                      64 MiB, else 1 (moev_tune_get returns 0 for MOEV_TUNE_COPY_UNROLL then) */
   MOEV_TUNE_ADAM_THREADS = 8,
   MOEV_TUNE_ADAM_UNROLL = 9,
   MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */
@@ -239,6 +242,8 @@ uint32_t ckpt_plan_n_segments(const moev_plan *plan, uint32_t slot);
 /* copies up to cap entries of the slot's segment table (host-computed offsets); returns the
  * number of segments of the slot or a negative error */
 int64_t ckpt_plan_segments(const moev_plan *plan, uint32_t slot, moev_segment *out, uint64_t cap);
+/* bytes of packed buffer one workgroup of snapshot_pack(slot) handles (0 if slot >= window) */
+uint64_t ckpt_plan_pack_tile_bytes(const moev_plan *plan, uint32_t slot);
 /* parameters updated by replay iteration i of a conversion: operators with slot <= i */
 uint64_t ckpt_plan_active_params(const moev_plan *plan, uint32_t i);
 

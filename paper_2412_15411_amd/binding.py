@@ -29,6 +29,7 @@ EXPORTS = [
     "moev_recovery_time", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
     "ckpt_plan_hash", "ckpt_plan_width", "ckpt_plan_format", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
+    "ckpt_plan_pack_tile_bytes",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
     "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
     "moev_copy_probe", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
@@ -100,6 +101,8 @@ def _load():
         getattr(lib, name).restype = u32
     lib.ckpt_plan_hash.argtypes = [vp]
     lib.ckpt_plan_hash.restype = u64
+    lib.ckpt_plan_pack_tile_bytes.argtypes = [vp, u32]
+    lib.ckpt_plan_pack_tile_bytes.restype = u64
     for name in ("ckpt_plan_width", "ckpt_plan_format"):
         getattr(lib, name).argtypes = [vp, u32]
         getattr(lib, name).restype = u32
@@ -278,6 +281,7 @@ def ckpt_plan_n_ops(plan): return _lib.ckpt_plan_n_ops(plan.handle)
 def ckpt_plan_n_tensors(plan): return _lib.ckpt_plan_n_tensors(plan.handle)
 def ckpt_plan_n_active(plan): return _lib.ckpt_plan_n_active(plan.handle)
 def ckpt_plan_hash(plan): return _lib.ckpt_plan_hash(plan.handle)
+def ckpt_plan_pack_tile_bytes(plan, slot): return _lib.ckpt_plan_pack_tile_bytes(plan.handle, slot)
 def ckpt_plan_width(plan, kind): return _lib.ckpt_plan_width(plan.handle, kind)
 def ckpt_plan_format(plan, kind): return _lib.ckpt_plan_format(plan.handle, kind)
 def ckpt_plan_packed_bytes(plan, slot): return _lib.ckpt_plan_packed_bytes(plan.handle, slot)

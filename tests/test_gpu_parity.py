@@ -142,10 +142,12 @@ def _many_segments():
 def test_device_layout_scan_matches_oracle(orc, dev, wl, align, tile):
     """The wavefront prefix sums on the device reproduce the oracle's serial layout exactly."""
     plan = make_plan(wl, align=align, tile=tile)
-    if tile is None:
-        tile = B.moev_tune_get(plan, B.TUNE_COPY_THREADS) * 16 * B.moev_tune_get(plan, B.TUNE_COPY_UNROLL)
     model = model_of(wl, align=align)
+    per_slot = tile is None
     for k in range(wl.window):
+        if per_slot:   # default shape: 256 threads x 16 bytes x (1 or 2 accesses per lane, chosen per slot)
+            tile = B.ckpt_plan_pack_tile_bytes(plan, k)
+            assert tile in (4096, 8192)
         segs, total = orc.layout(model, k)
         off, tiles, dev_total = B.ckpt_plan_device_layout(plan, k)
         assert off == [s[3] for s in segs]
