@@ -182,8 +182,14 @@ enum {
   MOEV_TUNE_ADAM_UNROLL = 9,
   MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */
   MOEV_TUNE_UNPACK_UNROLL = 11,
-  MOEV_TUNE_XCD_REGIONS = 12     /* one tile per workgroup: 1 (default) = each of the 8 XCDs sweeps a contiguous
+  MOEV_TUNE_XCD_REGIONS = 12,    /* one tile per workgroup: 1 (default) = each of the 8 XCDs sweeps a contiguous
                                     eighth of the tiles, 0 = consecutive workgroups take consecutive tiles */
+  MOEV_TUNE_PLAIN_DIVIDE_SQRT = 13 /* replay on low-precision state: 1 (default) = where every first and second moment
+                                    of a wavefront has a magnitude in [2^-60, 2^40) (and the bias corrections are in
+                                    [2^-20, 1], epsilon in [0, 2^20]) the three divisions and the square root run as the
+                                    compiler's IEEE sequences WITHOUT their rescaling and special-case steps, which do
+                                    nothing for such operands: same results, ~20% fewer instructions; 0 = always the
+                                    full sequences */
 };
 
 const char *moev_last_error(void);
@@ -377,6 +383,19 @@ int uplog_stats(moev_uplog *log, uint64_t *entries, uint64_t *bytes_in_use, uint
  * gather shape); blocks > 0: a fixed grid of that many workgroups, 32 KB per step. */
 int moev_copy_probe(void *d_dst, const void *d_src, size_t nbytes, uint32_t blocks, int nontemporal,
                     void *stream);
+
+/* ---- arithmetic self-check -----------------------------------------------------------------
+ * moev_arith_selfcheck: runs, on the GPU, the plain division / square-root sequences of
+ * MOEV_TUNE_PLAIN_DIVIDE_SQRT beside the compiler's full IEEE expansions and counts the inputs on
+ * which the two differ (the count must be 0).
+ *   what 0: n / divisor for the `count` consecutive FP32 bit patterns n starting at first_bits,
+ *           with both signs;
+ *   what 1: sqrt(x) for those patterns;
+ *   what 2: n / d for `count` pseudo-random pairs (seed), |n| in [2^-60, 2^60), d in [2^-30, 2^31).
+ * Allocates a counter, synchronises the stream, frees the counter.  Errors: MOEV_E_INVAL,
+ * MOEV_E_RANGE (patterns beyond the finite positive values), MOEV_E_HIP. */
+int moev_arith_selfcheck(int what, float divisor, uint32_t first_bits, uint64_t count, uint64_t seed,
+                         uint64_t *mismatches, void *stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ FMT_DEFAULT, FMT_F32, FMT_F16, FMT_BF16, FMT_E4M3, FMT_E5M2 = range(6)
 HEADER_BYTES = 256
 (TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL,
  TUNE_PERSISTENT, TUNE_COPY_THREADS, TUNE_COPY_UNROLL, TUNE_ADAM_THREADS, TUNE_ADAM_UNROLL,
- TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL, TUNE_XCD_REGIONS) = range(13)
+ TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL, TUNE_XCD_REGIONS, TUNE_PLAIN_DIVIDE_SQRT) = range(14)
 
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",
@@ -32,7 +32,7 @@ EXPORTS = [
     "ckpt_plan_pack_tile_bytes",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
     "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
-    "moev_copy_probe", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
+    "moev_copy_probe", "moev_arith_selfcheck", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
     "uplog_gc", "uplog_stats",
 ]
 
@@ -131,6 +131,7 @@ def _load():
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.convert_window_step.argtypes = [vp, u32, vp, vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
+    lib.moev_arith_selfcheck.argtypes = [C.c_int, C.c_float, u32, u64, u64, C.POINTER(u64), vp]
     lib.uplog_create.argtypes = [vp, C.c_size_t, u32, C.POINTER(vp)]
     lib.uplog_free.argtypes = [vp]
     lib.uplog_free.restype = None
@@ -376,6 +377,14 @@ def convert_window_step(plan, slot: int, h_pinned, d_packed, lr, beta1, beta2, e
     g = _ptr_array(grads)
     _check(_lib.convert_window_step(plan.handle, slot, _addr(h_pinned), _addr(d_packed), C.byref(adam),
                                     _addr(d_active_mask), g, C.byref(state.c), _stream(stream)))
+
+
+def moev_arith_selfcheck(what: int, divisor: float, first_bits: int, count: int, seed: int = 0, stream=None) -> int:
+    """-> number of inputs on which the plain division / square root differ from the full IEEE sequences."""
+    out = C.c_uint64()
+    _check(_lib.moev_arith_selfcheck(what, C.c_float(divisor), C.c_uint32(first_bits), C.c_uint64(count), C.c_uint64(seed),
+                                     C.byref(out), _stream(stream)))
+    return out.value
 
 
 def moev_copy_probe(d_dst, d_src, nbytes: int, blocks: int = 0, nontemporal: int = 1, stream=None):

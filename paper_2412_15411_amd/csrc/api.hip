@@ -86,6 +86,7 @@ struct moev_plan {
   int64_t adam_max_blocks = 0;
   int64_t nontemporal = 1;
   int64_t xcd_regions = 1;           // one tile per workgroup: contiguous eighth of the tiles per XCD
+  int64_t plain_divide_sqrt = 1;     // low-precision replay: plain division / square root sequences where in range
 
   // Accesses per lane of the pack of one slot.  Measured: one 16-byte access per lane is best when the slot's
   // segments are large (117-235 MB: 6.55 vs 6.25 TB/s) or all FP32 state; slots that gather many small
@@ -625,6 +626,10 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   } else if (low_precision) {
     a.scales = adam->d_scales;
     for (int k = 0; k < 4; ++k) a.fmt[k] = h.fmt[k];
+    // the plain sequences hold for moments in [2^-60, 2^40) if the other operands are ordinary too
+    const bool ordinary = a.bc1 >= 0x1p-20f && a.bc1 <= 1.0f && a.bc2 >= 0x1p-20f && a.bc2 <= 1.0f && a.eps >= 0.0f &&
+                          a.eps <= 0x1p20f;
+    a.plain_divide_sqrt = (p->plain_divide_sqrt && ordinary) ? 1u : 0u;
     MOEV_HIP(moev::launch_adam_lp(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   } else {
     MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
@@ -662,12 +667,14 @@ int ckpt_plan(const moev_plan_cfg* cfg, moev_plan** out) {
       delete pl;
       return fail(MOEV_E_INVAL, "ckpt_plan: slot too large");
     }
-  // Replay launch shape: state stored in 6 bytes per parameter or fewer keeps too few bytes in flight with one
-  // 16-byte gradient access per lane; two accesses per lane and 128 threads measured best there.
+  // Replay launch shape for state stored narrower than FP32 (measured on a Mixtral-shaped layer): 128 threads
+  // for 6 bytes of master + moments per parameter or fewer, and two accesses per lane at 4 bytes (too few bytes
+  // are in flight there with one 16-byte gradient access per lane).
   const auto& h = pl->host;
-  if (!fp32_regime(h) && h.width[MOEV_KIND_MASTER] + h.width[MOEV_KIND_ADAM_M] + h.width[MOEV_KIND_ADAM_V] <= 6) {
+  const uint32_t state_bytes = h.width[MOEV_KIND_MASTER] + h.width[MOEV_KIND_ADAM_M] + h.width[MOEV_KIND_ADAM_V];
+  if (!fp32_regime(h) && state_bytes <= 6) {
     pl->adam_threads = 128;
-    pl->adam_unroll = 2;
+    pl->adam_unroll = state_bytes <= 4 ? 2 : 1;
   }
   compute_host_tiles(pl);
   *out = pl;
@@ -827,6 +834,9 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
     case MOEV_TUNE_XCD_REGIONS:
       p->xcd_regions = value ? 1 : 0;
       break;
+    case MOEV_TUNE_PLAIN_DIVIDE_SQRT:
+      p->plain_divide_sqrt = value ? 1 : 0;
+      break;
     case MOEV_TUNE_COPY_THREADS:
       if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->copy_unroll)))
         return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
@@ -877,6 +887,7 @@ int64_t moev_tune_get(const moev_plan* p, int knob) {
     case MOEV_TUNE_NONTEMPORAL: return p->nontemporal;
     case MOEV_TUNE_PERSISTENT: return p->persistent;
     case MOEV_TUNE_XCD_REGIONS: return p->xcd_regions;
+    case MOEV_TUNE_PLAIN_DIVIDE_SQRT: return p->plain_divide_sqrt;
     case MOEV_TUNE_COPY_THREADS: return p->copy_threads;
     case MOEV_TUNE_COPY_UNROLL: return p->copy_unroll_auto ? 0 : p->copy_unroll;
     case MOEV_TUNE_UNPACK_THREADS: return p->unpack_threads;
@@ -930,6 +941,25 @@ int ckpt_plan_device_status(moev_plan* p, void* stream) {
     if (status == 2u) return fail(MOEV_E_INVAL, "convert_replay skipped an active operator whose gradient pointer was null");
     return fail(MOEV_E_MISMATCH, "a device-resident snapshot was refused by restore_unpack (foreign header)");
   }
+  return MOEV_OK;
+}
+
+int moev_arith_selfcheck(int what, float divisor, uint32_t first_bits, uint64_t count, uint64_t seed, uint64_t* mismatches,
+                         void* stream) {
+  if (what < 0 || what > 2 || !mismatches) return fail(MOEV_E_INVAL, "moev_arith_selfcheck: bad argument");
+  if (what != 2 && static_cast<uint64_t>(first_bits) + count > 0x7f800000ull)
+    return fail(MOEV_E_RANGE, "moev_arith_selfcheck: the patterns must be finite positive values");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned long long* d_count = nullptr;
+  MOEV_HIP(hipMalloc(reinterpret_cast<void**>(&d_count), sizeof(unsigned long long)));
+  unsigned long long host_count = 0;
+  hipError_t e = hipMemcpyAsync(d_count, &host_count, sizeof host_count, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = moev::launch_arith_check(static_cast<uint32_t>(what), divisor, first_bits, count, seed, d_count, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(&host_count, d_count, sizeof host_count, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(d_count);
+  if (e != hipSuccess) return fail(MOEV_E_HIP, "moev_arith_selfcheck: %s", hipGetErrorString(e));
+  *mismatches = host_count;
   return MOEV_OK;
 }
 

@@ -408,6 +408,46 @@ __device__ __forceinline__ void adam_element(float& p, float& m, float& v, float
   p = p - c.lr * (m_hat / denom);
 }
 
+// ---- correctly rounded division and square root for operands in a middle exponent range ----
+// hipcc expands an IEEE FP32 division n / d into: rescaling of both operands (v_div_scale_f32 twice), a
+// reciprocal estimate, one Newton step on it, a quotient estimate, two residual corrections with fused
+// multiply-adds, the final fused step that also undoes the rescaling (v_div_fmas_f32) and the fix-up of
+// the special cases (v_div_fixup_f32).  When neither operand is zero, infinite, NaN or subnormal, the
+// exponents differ by less than 96, the numerator is at least 2^-103 and neither 1/d nor n/d is
+// subnormal, nothing is rescaled or fixed up, and the sequence reduces to the one below: the same
+// instructions on the same values, hence the same (correctly rounded) quotient.  The reciprocal part
+// depends on the divisor alone, so a divisor shared by all elements (a bias correction) pays it once.
+struct Recip {
+  float d, r;  // the divisor and its refined reciprocal
+};
+__device__ __forceinline__ Recip refined_reciprocal(float d) {
+  const float r0 = __builtin_amdgcn_rcpf(d);
+  const float e = __builtin_fmaf(-d, r0, 1.0f);
+  return Recip{d, __builtin_fmaf(e, r0, r0)};
+}
+__device__ __forceinline__ float divide_in_range(float n, const Recip& k) {
+  const float q0 = n * k.r;
+  const float e1 = __builtin_fmaf(-k.d, q0, n);
+  const float q1 = __builtin_fmaf(e1, k.r, q0);
+  const float e2 = __builtin_fmaf(-k.d, q1, n);
+  return __builtin_fmaf(e2, k.r, q1);
+}
+// Likewise the square root: hipcc's expansion scales arguments below 2^-96 up and the result back,
+// and passes zero and infinity through; in between it is the hardware estimate moved by at most one
+// unit in the last place according to the signs of two exact residuals.
+__device__ __forceinline__ float sqrt_in_range(float x) {
+  const float s = __builtin_amdgcn_sqrtf(x);
+  const float s_down = __uint_as_float(__float_as_uint(s) - 1u), s_up = __uint_as_float(__float_as_uint(s) + 1u);
+  const float r_down = __builtin_fmaf(-s_down, s, x), r_up = __builtin_fmaf(-s_up, s, x);
+  float out = r_down <= 0.0f ? s_down : s;
+  out = r_up > 0.0f ? s_up : out;
+  return out;
+}
+// Magnitudes in [2^-60, 2^40): with bias corrections in [2^-20, 1] and epsilon in [0, 2^20] every
+// division and the square root of the step then stay inside the ranges above
+// (m_hat, v_hat in [2^-60, 2^60), sqrt in [2^-30, 2^30), denominator in [2^-30, 2^31)).
+constexpr uint32_t kRangeLo = (127u - 60u) << 23, kRangeHi = (127u + 40u) << 23;
+
 #define MOEV_ADAM_TABLES                                                                              \
   const uint32_t *__restrict__ tile_start, const uint64_t *__restrict__ numel_of,                     \
       const uint32_t *__restrict__ op_of_tensor, const uint8_t *__restrict__ mask,                    \
@@ -673,13 +713,46 @@ struct LpScales {
 template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC>
 __device__ __forceinline__ void adam_lp_quad(typename Fmt<FP>::Quad& p, typename Fmt<FM>::Quad& m, typename Fmt<FV>::Quad& v,
                                              typename Fmt<FC>::Quad& cw, const f32x4& g, const LpScales& sc,
-                                             const AdamConst& c) {
+                                             const AdamConst& c, bool fast, const Recip& k1, const Recip& k2) {
   float pf[4], mf[4], vf[4];
   Fmt<FP>::widen(p, sc.inv[0], pf);
   Fmt<FM>::widen(m, sc.inv[1], mf);
   Fmt<FV>::widen(v, sc.inv[2], vf);
+  // the step of adam_element(), with the divisions and the square root taken in their plain form when
+  // every moment of every lane of the wavefront is in range (the usual case; the decision is uniform)
+  uint32_t lo = ~0u, hi = 0u;
+  if (c.has_decay) {
+    asm volatile("");  // keeps this a branch (uniform, usually not taken) instead of three selected instructions per element
 #pragma unroll
-  for (int e = 0; e < 4; ++e) adam_element(pf[e], mf[e], vf[e], g[e], c);
+    for (int e = 0; e < 4; ++e) pf[e] = pf[e] - c.decay * pf[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    mf[e] = c.beta1 * mf[e] + c.one_minus_beta1 * g[e];
+    const float g2 = g[e] * g[e];
+    vf[e] = c.beta2 * vf[e] + c.one_minus_beta2 * g2;
+    const uint32_t mb = __float_as_uint(mf[e]) & 0x7fffffffu, vb = __float_as_uint(vf[e]);
+    lo = min(lo, min(mb, vb));
+    hi = max(hi, max(mb, vb));
+  }
+  const bool out_of_range = lo < kRangeLo || hi >= kRangeHi;
+  if (fast && __builtin_amdgcn_ballot_w64(out_of_range) == 0) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float m_hat = divide_in_range(mf[e], k1);
+      const float v_hat = divide_in_range(vf[e], k2);
+      const float denom = sqrt_in_range(v_hat) + c.eps;
+      pf[e] = pf[e] - c.lr * divide_in_range(m_hat, refined_reciprocal(denom));
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float m_hat = mf[e] / c.bc1;
+      const float v_hat = vf[e] / c.bc2;
+      const float denom = sqrtf(v_hat) + c.eps;
+      pf[e] = pf[e] - c.lr * (m_hat / denom);
+    }
+  }
   p = Fmt<FP>::narrow(pf, sc.s[0]);
   m = Fmt<FM>::narrow(mf, sc.s[1]);
   v = Fmt<FV>::narrow(vf, sc.s[2]);
@@ -711,7 +784,8 @@ __device__ __forceinline__ void store_first(uint8_t* base, uint64_t e, const typ
 template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC, uint32_t T, uint32_t U, bool NT>
 __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V, const float* __restrict__ G,
                                               uint8_t* __restrict__ C, uint64_t begin, uint64_t end, const LpScales& sc,
-                                              const AdamConst& c) {
+                                              const AdamConst& c, bool fast) {
+  const Recip k1 = refined_reciprocal(c.bc1), k2 = refined_reciprocal(c.bc2);
   using QP = typename Fmt<FP>::Quad;
   using QM = typename Fmt<FM>::Quad;
   using QV = typename Fmt<FV>::Quad;
@@ -737,7 +811,7 @@ __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V
       const uint64_t i = base + 4ull * T * u;
       if (i + 4 <= end) {
         QC cw;
-        adam_lp_quad<FP, FM, FV, FC>(p[u], m[u], v[u], cw, g[u], sc, c);
+        adam_lp_quad<FP, FM, FV, FC>(p[u], m[u], v[u], cw, g[u], sc, c, fast, k1, k2);
         st<NT>(reinterpret_cast<QP*>(P + i * WP), p[u]);
         st<NT>(reinterpret_cast<QM*>(M + i * WM), m[u]);
         st<NT>(reinterpret_cast<QV*>(V + i * WV), v[u]);
@@ -751,7 +825,7 @@ __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V
           QV v1 = quad_of_one<FV>(V, e);
           QC c1;
           const f32x4 g1 = {ld<false>(G + e), 0.0f, 0.0f, 0.0f};
-          adam_lp_quad<FP, FM, FV, FC>(p1, m1, v1, c1, g1, sc, c);
+          adam_lp_quad<FP, FM, FV, FC>(p1, m1, v1, c1, g1, sc, c, false, k1, k2);
           store_first<FP>(P, e, p1);
           store_first<FM>(M, e, m1);
           store_first<FV>(V, e, v1);
@@ -784,7 +858,44 @@ __global__ __launch_bounds__(T) void k_adam_lp(MOEV_ADAM_TABLES, const float* __
                                           static_cast<uint8_t*>(ptrs[2ull * a.n_tensors + t]),
                                           static_cast<const float*>(grads[t]),
                                           static_cast<uint8_t*>(ptrs[3ull * a.n_tensors + t]), begin, end, sc,
-                                          adam_const(a));
+                                          adam_const(a), a.plain_divide_sqrt != 0);
+}
+
+// ------------------------------------------------------------------------------------
+// self-check of divide_in_range / sqrt_in_range against hipcc's full IEEE expansions
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x += 0x9e3779b97f4a7c15ull;
+  x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ull;
+  x = (x ^ (x >> 27)) * 0x94d049bb133111ebull;
+  return x ^ (x >> 31);
+}
+
+// what 0: n / divisor for the `count` consecutive FP32 patterns n starting at first_bits, both signs;
+// what 1: sqrt(x) for those patterns; what 2: n / d for `count` pseudo-random pairs with |n| in
+// [2^-60, 2^60) and d in [2^-30, 2^31) (the ranges the replay's last division sees).
+__global__ __launch_bounds__(kThreads) void k_arith_check(uint32_t what, float divisor, uint32_t first_bits, uint64_t count,
+                                                          uint64_t seed, unsigned long long* __restrict__ mismatches) {
+  const Recip k = refined_reciprocal(divisor);
+  unsigned long long bad = 0;
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x; i < count;
+       i += static_cast<uint64_t>(gridDim.x) * kThreads) {
+    if (what == 0) {
+      const float n = __uint_as_float(first_bits + static_cast<uint32_t>(i));
+      bad += __float_as_uint(divide_in_range(n, k)) != __float_as_uint(n / divisor);
+      bad += __float_as_uint(divide_in_range(-n, k)) != __float_as_uint(-n / divisor);
+    } else if (what == 1) {
+      const float x = __uint_as_float(first_bits + static_cast<uint32_t>(i));
+      bad += __float_as_uint(sqrt_in_range(x)) != __float_as_uint(sqrtf(x));
+    } else {
+      const uint64_t h = mix64(seed ^ mix64(i));
+      const uint32_t n_bits = (static_cast<uint32_t>(h) % (120u << 23)) + ((127u - 60u) << 23);
+      const uint32_t d_bits = (static_cast<uint32_t>(h >> 32) % (61u << 23)) + ((127u - 30u) << 23);
+      const float n = __uint_as_float(n_bits | (static_cast<uint32_t>(h >> 31) & 0x80000000u)), d = __uint_as_float(d_bits);
+      bad += __float_as_uint(divide_in_range(n, refined_reciprocal(d))) != __float_as_uint(n / d);
+    }
+  }
+  if (bad) atomicAdd(mismatches, bad);
 }
 
 // ------------------------------------------------------------------------------------
@@ -947,6 +1058,12 @@ hipError_t launch_adam_lp(const AdamArgs& a, uint32_t blocks, uint32_t threads, 
 #undef MOEV_LP_X
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t launch_arith_check(uint32_t what, float divisor, uint32_t first_bits, uint64_t count, uint64_t seed,
+                              unsigned long long* d_mismatches, hipStream_t s) {
+  hipLaunchKernelGGL(k_arith_check, dim3(256 * 16), dim3(kThreads), 0, s, what, divisor, first_bits, count, seed, d_mismatches);
+  return hipGetLastError();
 }
 
 hipError_t launch_active_scan(const AdamArgs& a, uint32_t* d_out, hipStream_t s) {

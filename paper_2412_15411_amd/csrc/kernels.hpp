@@ -64,6 +64,8 @@ struct AdamArgs {
   // state stored in other formats than FP32 / FP32 / FP32 / BF16 (k_adam_lp only)
   const float* scales;         // [4 * n_tensors] kind-major per-tensor scales, or null = all 1
   uint32_t fmt[4];             // kFmt* of master, m, v, compute
+  uint32_t plain_divide_sqrt;  // 1: bias corrections and epsilon allow the divisions and the square root in their
+                               //    plain form wherever the moments are in the middle exponent range
   float lr, beta1, beta2, eps, one_minus_beta1, one_minus_beta2, bc1, bc2, decay;
 };
 
@@ -88,6 +90,11 @@ hipError_t launch_adam_fused(const AdamArgs& a, uint32_t blocks, uint32_t thread
 bool lp_formats_supported(const uint8_t fmt[4]);
 bool lp_shape_supported(uint32_t threads, uint32_t unroll);
 hipError_t launch_adam_lp(const AdamArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt, hipStream_t s);
+
+// Counts, into *d_mismatches, the inputs for which the plain division / square root sequences of the
+// low-precision replay differ from hipcc's full IEEE expansions (see k_arith_check).
+hipError_t launch_arith_check(uint32_t what, float divisor, uint32_t first_bits, uint64_t count, uint64_t seed,
+                              unsigned long long* d_mismatches, hipStream_t s);
 
 // fixed grid of 256-thread workgroups walking the tile list
 hipError_t launch_pack_persistent(const CopyArgs& a, uint32_t blocks, bool nt, hipStream_t s);

@@ -298,6 +298,51 @@ def test_low_precision_conversion_equals_dense_run(orc, dev, name):
     assert rebuilt.guards_intact()
 
 
+def test_plain_division_and_square_root_equal_the_full_sequences(dev):
+    """The replay takes its divisions and its square root without the rescaling / special-case steps of the
+    IEEE expansions where the operands are in a middle exponent range.  On the GPU, against the compiler's
+    full expansions: the square root for EVERY FP32 value of [2^-60, 2^60); the division by a bias
+    correction for EVERY numerator of that range (both signs) and 40 divisors; 2^32 random pairs for the
+    division by the per-element denominator."""
+    lo, n = (127 - 60) << 23, 120 << 23
+    assert B.moev_arith_selfcheck(1, 1.0, lo, n) == 0
+    divisors = [float(np.float32(1.0 - beta ** step)) for beta in (0.9, 0.95, 0.99, 0.999, 0.9999)
+                for step in (1, 2, 3, 11, 100, 1000, 100000)]
+    divisors += [1.0, 2.0 ** -20, float(np.nextafter(np.float32(2.0 ** -20), np.float32(1))), float(np.nextafter(np.float32(1), np.float32(0))),
+                 float(np.float32(1.0 / 3.0))]
+    for d in divisors:
+        assert 2.0 ** -20 <= d <= 1.0
+        assert B.moev_arith_selfcheck(0, d, lo, n) == 0, d
+    assert B.moev_arith_selfcheck(2, 1.0, 0, 1 << 32, seed=7) == 0
+    assert B.moev_arith_selfcheck(2, 1.0, 0, 1 << 30, seed=8) == 0
+    with pytest.raises(B.MoevError) as e:
+        B.moev_arith_selfcheck(1, 1.0, 0x7F000000, 1 << 30)
+    assert e.value.code == B.E_RANGE
+
+
+@pytest.mark.parametrize("name", ["fp8_fp8_fp8+fp16", "fp16_fp16_fp16+fp16"])
+def test_low_precision_replay_with_and_without_the_plain_sequences(orc, dev, name):
+    """Same inputs, knob on and off: both equal the oracle.  Values are in range for most wavefronts (plain
+    sequences) and a few tensors carry zeros, denormals and huge values (full sequences)."""
+    dtypes = VARIANTS[name]
+    wl = ragged_workload(19, max_numel=60000, with_empty=False)
+    table = scale_table(wl, dtypes, seed=3)
+    st_cpu = W.make_low_precision_state(wl, dtypes, [list(r) for r in table.tolist()], seed=2)
+    grads = W.make_grads(wl, 40, seed=2)
+    grads[0][::7] = 0.0            # zero gradients next to ordinary ones
+    grads[1][::5] = 1e-30          # squares underflow to zero / denormals
+    grads[2][::3] = 3e19           # squares overflow
+    st_cpu["m"][0].view(torch.uint8)[: st_cpu["m"][0].numel() * st_cpu["m"][0].element_size() // 2] = 0   # zero moments
+    mask_np = np.ones(wl.n_ops, dtype=np.uint8)
+    hp = orc.AdamHP(lr=1e-3, weight_decay=0.01)
+    for knob in (1, 0):
+        plan = lp_plan(wl, dtypes)
+        B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, knob)
+        assert B.moev_tune_get(plan, B.TUNE_PLAIN_DIVIDE_SQRT) == knob
+        ds, ref, fmts = run_both(orc, dev, wl, dtypes, st_cpu, table, grads, mask_np, hp, 40, plan)
+        assert_states_match(orc, ds, ref, fmts)
+
+
 def test_low_precision_replay_argument_errors(dev):
     wl = ragged_workload(2, max_numel=1000)
     mask = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
