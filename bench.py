@@ -623,6 +623,17 @@ def main():
                         "GBs": round(nbytes / (best / 1e3) / 1e9, 2)}
         ok = B.snapshot_peek(plan, k, host)["slot"] == k
         out["drain"]["header_ok"] = bool(ok)
+        # the same slot through a ring of four 64 MiB pinned chunks (hosts that cannot pin a whole slot)
+        chunk = 64 << 20
+        ring = [torch.empty(chunk, dtype=torch.uint8).pin_memory() for _ in range(4)]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for i, off in enumerate(range(0, nbytes, chunk)):
+            B.snapshot_drain_range(plan, k, packed[k], off, ring[i % 4], min(chunk, nbytes - off), side_stream=side)
+        e1.record(side)
+        side.synchronize()
+        out["drain"]["chunked_64MiB_GBs"] = round(nbytes / (e0.elapsed_time(e1) / 1e3) / 1e9, 2)
+        del ring
         if args.overlap:
             a = torch.randn(8192, 4096, dtype=torch.bfloat16, device=dev)
             b = torch.randn(4096, 2048, dtype=torch.bfloat16, device=dev)

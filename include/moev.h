@@ -289,6 +289,13 @@ int snapshot_pack(moev_plan *plan, uint32_t slot, uint64_t iter, const moev_stat
 int snapshot_drain(moev_plan *plan, uint32_t slot, const void *d_packed, void *h_pinned, size_t cap,
                    void *side_stream, void *pack_done, void *drained);
 
+/* snapshot_drain_range: the same for bytes [offset, offset + nbytes) of the slot's packed snapshot, for
+ * hosts that cannot pin a whole slot: the caller drains through a ring of pinned chunks, consuming
+ * (persisting, sending) each chunk after its `drained` event and reusing it.  MOEV_E_RANGE if the range
+ * leaves the slot's packed bytes. */
+int snapshot_drain_range(moev_plan *plan, uint32_t slot, const void *d_packed, uint64_t offset, void *h_pinned,
+                         size_t nbytes, void *side_stream, void *pack_done, void *drained);
+
 /* parse and validate a snapshot header that lies in HOST memory against the plan and slot.
  * Returns MOEV_OK, MOEV_E_MISMATCH or MOEV_E_INVAL; *out (optional) receives the fields. */
 int snapshot_peek(const moev_plan *plan, uint32_t slot, const void *h_packed, moev_header *out);

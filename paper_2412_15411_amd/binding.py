@@ -31,7 +31,7 @@ EXPORTS = [
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "ckpt_plan_pack_tile_bytes",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
-    "snapshot_pack", "snapshot_drain", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
+    "snapshot_pack", "snapshot_drain", "snapshot_drain_range", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
     "moev_copy_probe", "moev_arith_selfcheck", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
     "uplog_gc", "uplog_stats",
 ]
@@ -126,6 +126,7 @@ def _load():
     lib.ckpt_plan_device_status.argtypes = [vp, vp]
     lib.snapshot_pack.argtypes = [vp, u32, u64, C.POINTER(_State), vp, C.c_size_t, vp]
     lib.snapshot_drain.argtypes = [vp, u32, vp, vp, C.c_size_t, vp, vp, vp]
+    lib.snapshot_drain_range.argtypes = [vp, u32, vp, u64, vp, C.c_size_t, vp, vp, vp]
     lib.snapshot_peek.argtypes = [vp, u32, vp, C.POINTER(_Header)]
     lib.restore_unpack.argtypes = [vp, u32, vp, vp, C.POINTER(_State), vp, vp]
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
@@ -350,6 +351,12 @@ def snapshot_drain(plan, slot: int, d_packed, h_pinned, cap: Optional[int] = Non
         cap = h_pinned.numel() * h_pinned.element_size()
     _check(_lib.snapshot_drain(plan.handle, slot, _addr(d_packed), _addr(h_pinned), cap, _stream(side_stream),
                                _event(pack_done), _event(drained)))
+
+
+def snapshot_drain_range(plan, slot: int, d_packed, offset: int, h_pinned, nbytes: int, side_stream=None,
+                         pack_done=None, drained=None):
+    _check(_lib.snapshot_drain_range(plan.handle, slot, _addr(d_packed), offset, _addr(h_pinned), nbytes,
+                                     _stream(side_stream), _event(pack_done), _event(drained)))
 
 
 def snapshot_peek(plan, slot: int, h_packed) -> dict:

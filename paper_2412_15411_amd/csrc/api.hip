@@ -1021,6 +1021,24 @@ int snapshot_drain(moev_plan* p, uint32_t slot, const void* d_packed, void* h_pi
   return MOEV_OK;
 }
 
+int snapshot_drain_range(moev_plan* p, uint32_t slot, const void* d_packed, uint64_t offset, void* h_pinned, size_t nbytes,
+                         void* side_stream, void* pack_done, void* drained) {
+  if (!p || !d_packed || (!h_pinned && nbytes)) return fail(MOEV_E_INVAL, "snapshot_drain_range: null argument");
+  if (slot >= p->host.window)
+    return fail(MOEV_E_RANGE, "snapshot_drain_range: slot %u outside window %u", slot, p->host.window);
+  const uint64_t total = p->host.slots[slot].packed_bytes;
+  if (offset > total || nbytes > total - offset)
+    return fail(MOEV_E_RANGE, "snapshot_drain_range: bytes [%llu, %llu) are outside the slot's %llu packed bytes",
+                static_cast<unsigned long long>(offset), static_cast<unsigned long long>(offset + nbytes),
+                static_cast<unsigned long long>(total));
+  hipStream_t s = static_cast<hipStream_t>(side_stream);
+  if (pack_done) MOEV_HIP(hipStreamWaitEvent(s, static_cast<hipEvent_t>(pack_done), 0));
+  if (nbytes)
+    MOEV_HIP(hipMemcpyAsync(h_pinned, static_cast<const uint8_t*>(d_packed) + offset, nbytes, hipMemcpyDeviceToHost, s));
+  if (drained) MOEV_HIP(hipEventRecord(static_cast<hipEvent_t>(drained), s));
+  return MOEV_OK;
+}
+
 int snapshot_peek(const moev_plan* p, uint32_t slot, const void* h_packed, moev_header* out) {
   if (!p || !h_packed) return fail(MOEV_E_INVAL, "snapshot_peek: null argument");
   if (slot >= p->host.window) return fail(MOEV_E_RANGE, "snapshot_peek: slot outside window");

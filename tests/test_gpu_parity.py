@@ -359,6 +359,47 @@ def test_pack_drain_restore_roundtrip_through_pinned_host(orc, dev):
         side.synchronize()
 
 
+def test_drain_through_a_ring_of_pinned_chunks(orc, dev):
+    """A host that cannot pin a whole slot drains it in ranges through a small ring of pinned chunks; the
+    reassembled bytes equal the oracle's snapshot (ragged last chunk, empty range, ranges outside the slot)."""
+    wl = ragged_workload(27, max_numel=150000)
+    model, plan = model_of(wl), make_plan(wl)
+    st_cpu = W.make_state(wl, seed=9)
+    ds, ref_state = DeviceState(st_cpu, dev), state_of(st_cpu)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    chunk, n_chunks = 100_000, 3                     # not a multiple of anything
+    ring = [torch.empty(chunk, dtype=torch.uint8).pin_memory() for _ in range(n_chunks)]
+    events = [torch.cuda.Event() for _ in range(n_chunks)]
+    buf = packed_buffer(plan, dev)
+    for k in (0, wl.window - 1):
+        packed_done = torch.cuda.Event()
+        B.snapshot_pack(plan, k, 3, ds.state, buf, stream=main)
+        packed_done.record(main)
+        total = B.ckpt_plan_packed_bytes(plan, k)
+        out = np.empty(total, dtype=np.uint8)
+        offsets = list(range(0, total, chunk))
+        for i, off in enumerate(offsets):
+            slot_in_ring = i % n_chunks
+            if i >= n_chunks:                        # consume the chunk that is about to be reused
+                events[slot_in_ring].synchronize()
+                prev = offsets[i - n_chunks]
+                out[prev:prev + chunk] = ring[slot_in_ring].numpy()[:min(chunk, total - prev)]
+            n = min(chunk, total - off)
+            events[slot_in_ring].record(side)
+            B.snapshot_drain_range(plan, k, buf, off, ring[slot_in_ring], n, side_stream=side,
+                                   pack_done=packed_done if i == 0 else None, drained=events[slot_in_ring])
+        side.synchronize()
+        for i in range(max(0, len(offsets) - n_chunks), len(offsets)):
+            off = offsets[i]
+            out[off:off + chunk] = ring[i % n_chunks].numpy()[:min(chunk, total - off)]
+        assert out.tobytes() == orc.pack(model, k, 3, ref_state).tobytes()
+        B.snapshot_drain_range(plan, k, buf, total, None, 0, side_stream=side)          # empty range at the end
+        for off, n in ((total, 1), (0, total + 1), (total + 5, 0)):
+            with pytest.raises(B.MoevError) as e:
+                B.snapshot_drain_range(plan, k, buf, off, ring[0], n, side_stream=side)
+            assert e.value.code == B.E_RANGE
+
+
 def test_fresh_plan_used_on_two_streams_without_host_synchronisation(orc, dev):
     """The plan's device tables are built by its first call, on that call's stream; the next call runs on
     another stream, ordered only by the caller's event on the data.  Pack on stream A, unpack (into another
