@@ -55,6 +55,7 @@ def parse_args():
     ap.add_argument("--adam-blocks", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-regions", type=int, default=-1)
+    ap.add_argument("--plain-divide-sqrt", type=int, default=-1, help="0: always the full IEEE division / square-root sequences in the replay")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -418,6 +419,8 @@ def main():
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
     if args.xcd_regions >= 0:
         B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
+    if args.plain_divide_sqrt >= 0:
+        B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, args.plain_divide_sqrt)
     packed = [torch.empty(B.ckpt_plan_packed_bytes(plan, k), dtype=torch.uint8, device=dev) for k in range(wl.window)]
     mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()

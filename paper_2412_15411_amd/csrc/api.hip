@@ -596,6 +596,10 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
   a.decay = adam->lr * adam->weight_decay;
   a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
+  // the plain division / square-root sequences hold for moments in [2^-60, 2^40) if the other operands are ordinary too
+  const bool ordinary = a.bc1 >= 0x1p-20f && a.bc1 <= 1.0f && a.bc2 >= 0x1p-20f && a.bc2 <= 1.0f && a.eps >= 0.0f &&
+                        a.eps <= 0x1p20f;
+  a.plain_divide_sqrt = (p->plain_divide_sqrt && ordinary) ? 1u : 0u;
   const bool low_precision = !fp32_regime(h);
   if (p->persistent && !low_precision) {
     MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
@@ -626,10 +630,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   } else if (low_precision) {
     a.scales = adam->d_scales;
     for (int k = 0; k < 4; ++k) a.fmt[k] = h.fmt[k];
-    // the plain sequences hold for moments in [2^-60, 2^40) if the other operands are ordinary too
-    const bool ordinary = a.bc1 >= 0x1p-20f && a.bc1 <= 1.0f && a.bc2 >= 0x1p-20f && a.bc2 <= 1.0f && a.eps >= 0.0f &&
-                          a.eps <= 0x1p20f;
-    a.plain_divide_sqrt = (p->plain_divide_sqrt && ordinary) ? 1u : 0u;
+
     MOEV_HIP(moev::launch_adam_lp(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   } else {
     MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));

@@ -448,6 +448,46 @@ __device__ __forceinline__ float sqrt_in_range(float x) {
 // (m_hat, v_hat in [2^-60, 2^60), sqrt in [2^-30, 2^30), denominator in [2^-30, 2^31)).
 constexpr uint32_t kRangeLo = (127u - 60u) << 23, kRangeHi = (127u + 40u) << 23;
 
+// The step of adam_element() on four elements at once, with the divisions and the square root taken in
+// their plain form when every updated moment of every active lane of the wavefront is in range (the usual
+// case; the decision is uniform across the wavefront, so there is no divergence).
+__device__ __forceinline__ void adam_quad(float (&p)[4], float (&m)[4], float (&v)[4], const f32x4& g, const AdamConst& c,
+                                          bool plain, const Recip& k1, const Recip& k2) {
+  uint32_t lo = ~0u, hi = 0u;
+  if (c.has_decay) {
+    asm volatile("");  // keeps this a branch (uniform, usually not taken) instead of three selected instructions per element
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = p[e] - c.decay * p[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    m[e] = c.beta1 * m[e] + c.one_minus_beta1 * g[e];
+    const float g2 = g[e] * g[e];
+    v[e] = c.beta2 * v[e] + c.one_minus_beta2 * g2;
+    const uint32_t mb = __float_as_uint(m[e]) & 0x7fffffffu, vb = __float_as_uint(v[e]);
+    lo = min(lo, min(mb, vb));
+    hi = max(hi, max(mb, vb));
+  }
+  const bool out_of_range = lo < kRangeLo || hi >= kRangeHi;
+  if (plain && __builtin_amdgcn_ballot_w64(out_of_range) == 0) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float m_hat = divide_in_range(m[e], k1);
+      const float v_hat = divide_in_range(v[e], k2);
+      const float denom = sqrt_in_range(v_hat) + c.eps;
+      p[e] = p[e] - c.lr * divide_in_range(m_hat, refined_reciprocal(denom));
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float m_hat = m[e] / c.bc1;
+      const float v_hat = v[e] / c.bc2;
+      const float denom = sqrtf(v_hat) + c.eps;
+      p[e] = p[e] - c.lr * (m_hat / denom);
+    }
+  }
+}
+
 #define MOEV_ADAM_TABLES                                                                              \
   const uint32_t *__restrict__ tile_start, const uint64_t *__restrict__ numel_of,                     \
       const uint32_t *__restrict__ op_of_tensor, const uint8_t *__restrict__ mask,                    \
@@ -459,7 +499,9 @@ constexpr uint32_t kRangeLo = (127u - 60u) << 23, kRangeHi = (127u + 40u) << 23;
 template <uint32_t T, uint32_t U, bool NT>
 __device__ __forceinline__ void adam_range(const float* Ps, const float* Ms, const float* Vs,
                                            const float* __restrict__ G, float* P, float* M, float* V,
-                                           uint16_t* __restrict__ C, uint64_t begin, uint64_t end, const AdamConst& c) {
+                                           uint16_t* __restrict__ C, uint64_t begin, uint64_t end, const AdamConst& c,
+                                           bool plain) {
+  const Recip k1 = refined_reciprocal(c.bc1), k2 = refined_reciprocal(c.bc2);
   for (uint64_t base = begin + 4ull * threadIdx.x; base < end; base += 4ull * T * U) {
     f32x4 p[U], m[U], v[U], g[U];
 #pragma unroll
@@ -476,14 +518,12 @@ __device__ __forceinline__ void adam_range(const float* Ps, const float* Ms, con
     for (uint32_t u = 0; u < U; ++u) {
       const uint64_t i = base + 4ull * T * u;
       if (i + 4 <= end) {
-#pragma unroll
-        for (uint32_t e = 0; e < 4; ++e) {
-          float pe = p[u][e], me = m[u][e], ve = v[u][e];
-          adam_element(pe, me, ve, g[u][e], c);
-          p[u][e] = pe;
-          m[u][e] = me;
-          v[u][e] = ve;
-        }
+        float pe[4] = {p[u].x, p[u].y, p[u].z, p[u].w}, me[4] = {m[u].x, m[u].y, m[u].z, m[u].w},
+              ve[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        adam_quad(pe, me, ve, g[u], c, plain, k1, k2);
+        p[u] = f32x4{pe[0], pe[1], pe[2], pe[3]};
+        m[u] = f32x4{me[0], me[1], me[2], me[3]};
+        v[u] = f32x4{ve[0], ve[1], ve[2], ve[3]};
         st<NT>(reinterpret_cast<f32x4*>(P + i), p[u]);
         st<NT>(reinterpret_cast<f32x4*>(M + i), m[u]);
         st<NT>(reinterpret_cast<f32x4*>(V + i), v[u]);
@@ -519,7 +559,8 @@ __global__ __launch_bounds__(T) void k_adam_direct(MOEV_ADAM_TABLES, const AdamA
   float* M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
   float* V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
   uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
-  adam_range<T, U, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a));
+  adam_range<T, U, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a),
+                       a.plain_divide_sqrt != 0);
 }
 
 // Fused snapshot load + replay (steps 1+2, 3+4, 5+6 of the Sec. 3.3 walk-through in one pass): for
@@ -552,7 +593,8 @@ __global__ __launch_bounds__(T) void k_adam_fused(MOEV_ADAM_TABLES, const uint64
     Ms = reinterpret_cast<const float*>(a.packed + src_off[static_cast<uint64_t>(a.n_tensors) + t]);
     Vs = reinterpret_cast<const float*>(a.packed + src_off[2ull * a.n_tensors + t]);
   }
-  adam_range<T, U, NT>(Ps, Ms, Vs, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a));
+  adam_range<T, U, NT>(Ps, Ms, Vs, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, adam_const(a),
+                       a.plain_divide_sqrt != 0);
 }
 
 // fixed grid over the static (all tensors) tile list; frozen tensors are jumped over
@@ -582,7 +624,8 @@ __global__ __launch_bounds__(kThreads) void k_adam_persistent(MOEV_ADAM_TABLES, 
     float* M = static_cast<float*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]);
     float* V = static_cast<float*>(ptrs[2ull * a.n_tensors + t]);
     uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
-    adam_range<kThreads, 2, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, c);
+    adam_range<kThreads, 2, NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, begin, end, c,
+                                a.plain_divide_sqrt != 0);
     tile += gridDim.x;
   }
 }
@@ -718,41 +761,7 @@ __device__ __forceinline__ void adam_lp_quad(typename Fmt<FP>::Quad& p, typename
   Fmt<FP>::widen(p, sc.inv[0], pf);
   Fmt<FM>::widen(m, sc.inv[1], mf);
   Fmt<FV>::widen(v, sc.inv[2], vf);
-  // the step of adam_element(), with the divisions and the square root taken in their plain form when
-  // every moment of every lane of the wavefront is in range (the usual case; the decision is uniform)
-  uint32_t lo = ~0u, hi = 0u;
-  if (c.has_decay) {
-    asm volatile("");  // keeps this a branch (uniform, usually not taken) instead of three selected instructions per element
-#pragma unroll
-    for (int e = 0; e < 4; ++e) pf[e] = pf[e] - c.decay * pf[e];
-  }
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    mf[e] = c.beta1 * mf[e] + c.one_minus_beta1 * g[e];
-    const float g2 = g[e] * g[e];
-    vf[e] = c.beta2 * vf[e] + c.one_minus_beta2 * g2;
-    const uint32_t mb = __float_as_uint(mf[e]) & 0x7fffffffu, vb = __float_as_uint(vf[e]);
-    lo = min(lo, min(mb, vb));
-    hi = max(hi, max(mb, vb));
-  }
-  const bool out_of_range = lo < kRangeLo || hi >= kRangeHi;
-  if (fast && __builtin_amdgcn_ballot_w64(out_of_range) == 0) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float m_hat = divide_in_range(mf[e], k1);
-      const float v_hat = divide_in_range(vf[e], k2);
-      const float denom = sqrt_in_range(v_hat) + c.eps;
-      pf[e] = pf[e] - c.lr * divide_in_range(m_hat, refined_reciprocal(denom));
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float m_hat = mf[e] / c.bc1;
-      const float v_hat = vf[e] / c.bc2;
-      const float denom = sqrtf(v_hat) + c.eps;
-      pf[e] = pf[e] - c.lr * (m_hat / denom);
-    }
-  }
+  adam_quad(pf, mf, vf, g, c, fast, k1, k2);
   p = Fmt<FP>::narrow(pf, sc.s[0]);
   m = Fmt<FM>::narrow(mf, sc.s[1]);
   v = Fmt<FV>::narrow(vf, sc.s[2]);
