@@ -359,3 +359,88 @@ def test_low_precision_replay_argument_errors(dev):
     with pytest.raises(B.MoevError) as e:
         B.convert_replay(plan, 1e-4, 0.9, 0.95, 1e-8, 0.0, 11, mask, [None] * wl.n_tensors, st)
     assert e.value.code == B.E_INVAL
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_plans_whole_window(orc, dev, seed):
+    """Seeded random plans: operator count, tensor sizes (ragged, some empty), window, schedule order, segment
+    alignment, storage formats (FP32 regime or one of the low-precision combinations), launch shapes, scales.
+    Dense run with snapshots, then conversion from a poisoned state: equals the dense run and the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    n_ops = int(rng.integers(1, 14))
+    window = min(n_ops, 1 + seed % 4)
+    tensors = []
+    for e in range(n_ops):
+        for _ in range(int(rng.integers(1, 4))):
+            n = int(rng.choice([0, 1, 3, 4, 5, 63, 64, 257, 1000, 4097, 20000, 70001]))
+            tensors.append((e, n))
+    slots = [int(x) for x in rng.integers(0, window, size=n_ops)]
+    for k in range(window):                       # every slot of the window is used
+        slots[int(rng.integers(0, n_ops))] = k if n_ops >= window else slots[0]
+    window = max(slots) + 1
+    order = sorted(range(n_ops), key=lambda e: (slots[e], int(rng.integers(0, 1000))))
+    wl = W.Workload(f"random{seed}", tensors, slots, window, order=order, lr=float(rng.choice([1e-4, 1e-2])),
+                    weight_decay=float(rng.choice([0.0, 0.05])))
+    names = [None] + list(VARIANTS)
+    name = names[int(rng.integers(0, len(names)))]
+    align = int(rng.choice([16, 64, 256, 1024]))
+    hp = hp_of(wl)
+    if name is None:
+        dtypes = (torch.float32, torch.float32, torch.float32, torch.bfloat16)
+        st_cpu, table = W.make_state(wl, seed=seed), None
+        plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, align=align)
+        model = model_of(wl, align=align)
+    else:
+        dtypes = VARIANTS[name]
+        table = scale_table(wl, dtypes, seed=seed, odd=bool(rng.integers(0, 2)))
+        st_cpu = W.make_low_precision_state(wl, dtypes, [list(r) for r in table.tolist()], seed=seed)
+        plan = lp_plan(wl, dtypes, align=align)
+        model = model_of(wl, align=align, formats=tuple(ORACLE_FMT_OF_DTYPE[d] for d in dtypes))
+    fmts = tuple(ORACLE_FMT_OF_DTYPE[d] for d in dtypes)
+    shapes = [(64, 1), (64, 2), (128, 1), (128, 2), (256, 1), (256, 2)]
+    th, un = shapes[int(rng.integers(0, len(shapes)))]
+    B.moev_tune(plan, B.TUNE_ADAM_UNROLL, 1)
+    B.moev_tune(plan, B.TUNE_ADAM_THREADS, th)
+    B.moev_tune(plan, B.TUNE_ADAM_UNROLL, un)
+    B.moev_tune(plan, B.TUNE_XCD_REGIONS, int(rng.integers(0, 2)))
+    d_scales = torch.from_numpy(table).to(dev) if table is not None else None
+    live = DeviceState(st_cpu, dev)
+    ref = orc.State(*[[np_of(t) for t in st_cpu[k]] for k in KINDS])
+    everyone = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    ones = np.ones(wl.n_ops, dtype=np.uint8)
+    bufs = []
+    for k in range(wl.window):
+        bufs.append(packed_buffer(plan, dev, k))
+        B.snapshot_pack(plan, k, wl.t0 + k, live.state, bufs[k])
+        torch.cuda.synchronize()
+        exp = orc.pack(model, k, wl.t0 + k, ref)
+        assert bufs[k].cpu().numpy()[:exp.size].tobytes() == exp.tobytes(), f"snapshot {k}"
+        g = W.make_grads(wl, wl.t0 + k + 1, seed=seed)
+        B.convert_replay(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, wl.t0 + k + 1, everyone,
+                         [x.to(dev) for x in g], live.state, d_scales=d_scales)
+        orc.replay_step(model, hp, wl.t0 + k + 1, ones, [x.numpy() for x in g], ref, table)
+    torch.cuda.synchronize()
+    assert_states_match(orc, live, ref, fmts)
+    rebuilt = DeviceState(st_cpu, dev)
+    for kind in KINDS:
+        for v in rebuilt.views[kind]:
+            v.view(torch.uint8).fill_(0xFF)
+    mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
+    for i in range(wl.window):
+        g = W.make_grads(wl, wl.t0 + i + 1, seed=seed)
+        dg = [x.to(dev) if wl.slot_of_op[wl.tensors[t][0]] <= i else None for t, x in enumerate(g)]
+        if int(rng.integers(0, 2)):
+            B.convert_window_step(plan, i, None, bufs[i], hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay,
+                                  wl.t0 + i + 1, mask, dg, rebuilt.state, d_scales=d_scales)
+        else:
+            B.restore_unpack(plan, i, None, bufs[i], rebuilt.state, mask)
+            B.convert_replay(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, wl.t0 + i + 1, mask, dg,
+                             rebuilt.state, d_scales=d_scales)
+    torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan)
+    assert bool(mask.cpu().all())
+    a, b = rebuilt.to_oracle(), live.to_oracle()
+    for kind in KINDS:
+        for t, (x, y) in enumerate(zip(a.kinds()[kind], b.kinds()[kind])):
+            assert x.tobytes() == y.tobytes(), (kind, t)
+    assert rebuilt.guards_intact() and live.guards_intact()
