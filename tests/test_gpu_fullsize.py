@@ -136,48 +136,66 @@ def test_fullsize_fine_grained_pack_unpack(orc, dev):
     run_pack_unpack_fullsize(orc, dev, W.fine_grained_stack(), slots=(0, 15))
 
 
+def _replay_sampled(orc, dev, wl, it_index, extra_windows=()):
+    """convert_replay at full size with the mask of replay iteration `it_index`; sampled element windows of
+    every tensor (first / last / random / the given extra ones) against the oracle's Adam."""
+    hp = hp_of(wl)
+    plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+    st = W.make_state(wl, seed=3, device=dev)
+    state = B.State(*[st[k] for k in KINDS])
+    step = wl.t0 + it_index + 1
+    active = [1 if s <= it_index else 0 for s in wl.slot_of_op]
+    mask = torch.tensor(active, dtype=torch.uint8, device=dev)
+    full = W.make_grads(wl, step, seed=3, device=dev)
+    grads = [g if active[wl.tensors[t][0]] else None for t, g in enumerate(full)]
+    rng = np.random.default_rng(1)
+    width = 4096
+    before = {}
+    for t, (op, numel) in enumerate(wl.tensors):
+        wins = [(a // 4, b // 4) for a, b in sample_windows(numel * 4, rng, 1 if wl.n_tensors > 100 else 6, width * 4)]
+        wins += [(a, b) for a, b in extra_windows if b <= numel]
+        before[t] = [(a, b, {k: st[k][t][a:b].clone() for k in KINDS}, full[t][a:b].clone()) for a, b in wins]
+    B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, step, mask, grads, state)
+    torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan)
+    worst = 0.0
+    for t, (op, numel) in enumerate(wl.tensors):
+        for a, b, old, g in before[t]:
+            now = {k: np_of(st[k][t][a:b]) for k in KINDS}
+            if not active[op]:
+                for k in KINDS:
+                    assert now[k].tobytes() == np_of(old[k]).tobytes(), f"frozen tensor {t} changed"
+                continue
+            p, m, v, c = np_of(old["master"]), np_of(old["m"]), np_of(old["v"]), np_of(old["compute"])
+            orc.adam_tensor(p, m, v, np_of(g), c, hp, step)
+            for name, ref in (("master", p), ("m", m), ("v", v)):
+                err = np.max(np.abs(now[name].astype(np.float64) - ref.astype(np.float64)) /
+                             np.maximum(np.abs(ref.astype(np.float64)), 1e-30))
+                worst = max(worst, float(err))
+                assert err <= 1e-6, f"{wl.name} tensor {t} {name} window {a}: rel err {err}"
+            same = now["master"].view(np.uint32) == p.view(np.uint32)
+            assert np.array_equal(now["compute"][same], c[same])
+    print(f"{wl.name}: worst relative error over sampled windows {worst:.3g}")
+    del st, state, full, grads, before
+    _release()
+
+
 def test_fullsize_replay_sampled(orc, dev):
     """configs[1] and configs[4] shapes: convert_replay at full size with the mask of a mid-window
     iteration; sampled windows of every tensor (first / last / random) against the oracle's Adam."""
     for wl, it_index in ((W.mixtral_layer(), 5), (W.conversion_stress(), 9)):
-        hp = hp_of(wl)
-        plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
-        st = W.make_state(wl, seed=3, device=dev)
-        state = B.State(*[st[k] for k in KINDS])
-        step = wl.t0 + it_index + 1
-        active = [1 if s <= it_index else 0 for s in wl.slot_of_op]
-        mask = torch.tensor(active, dtype=torch.uint8, device=dev)
-        full = W.make_grads(wl, step, seed=3, device=dev)
-        grads = [g if active[wl.tensors[t][0]] else None for t, g in enumerate(full)]
-        rng = np.random.default_rng(1)
-        width = 4096
-        before = {}
-        for t, (op, numel) in enumerate(wl.tensors):
-            wins = [(a // 4, b // 4) for a, b in sample_windows(numel * 4, rng, 1 if wl.n_tensors > 100 else 6, width * 4)]
-            before[t] = [(a, b, {k: st[k][t][a:b].clone() for k in KINDS}, full[t][a:b].clone()) for a, b in wins]
-        B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, step, mask, grads, state)
-        torch.cuda.synchronize()
-        B.ckpt_plan_device_status(plan)
-        worst = 0.0
-        for t, (op, numel) in enumerate(wl.tensors):
-            for a, b, old, g in before[t]:
-                now = {k: np_of(st[k][t][a:b]) for k in KINDS}
-                if not active[op]:
-                    for k in KINDS:
-                        assert now[k].tobytes() == np_of(old[k]).tobytes(), f"frozen tensor {t} changed"
-                    continue
-                p, m, v, c = np_of(old["master"]), np_of(old["m"]), np_of(old["v"]), np_of(old["compute"])
-                orc.adam_tensor(p, m, v, np_of(g), c, hp, step)
-                for name, ref in (("master", p), ("m", m), ("v", v)):
-                    err = np.max(np.abs(now[name].astype(np.float64) - ref.astype(np.float64)) /
-                                 np.maximum(np.abs(ref.astype(np.float64)), 1e-30))
-                    worst = max(worst, float(err))
-                    assert err <= 1e-6, f"{wl.name} tensor {t} {name} window {a}: rel err {err}"
-                same = now["master"].view(np.uint32) == p.view(np.uint32)
-                assert np.array_equal(now["compute"][same], c[same])
-        print(f"{wl.name}: worst relative error over sampled windows {worst:.3g}")
-        del st, state, full, grads, before
-        _release()
+        _replay_sampled(orc, dev, wl, it_index)
+
+
+def test_tensors_beyond_4_GiB(orc, dev):
+    """Maximum sizes: single tensors of 5.0 and 4.4 GB per FP32 kind (ragged lengths), so that byte offsets
+    INSIDE one segment pass 2^32 and element indices pass 2^30: pack / unpack (sampled windows, word sums,
+    poison) and the replay on windows around those boundaries and at the ragged tails."""
+    wl = W.Workload("huge", [(0, 1_250_000_003), (1, 1_100_000_001)], [0, 1], 2)
+    run_pack_unpack_fullsize(orc, dev, wl, slots=(0, 1), seed=2)
+    edge = 1 << 30
+    _replay_sampled(orc, dev, wl, 1, extra_windows=[(edge - 2048, edge + 2048), (edge - 3, edge + 5),
+                                                    (1_100_000_001 - 9, 1_100_000_001), (1_250_000_003 - 7, 1_250_000_003)])
 
 
 @pytest.mark.parametrize("regime", ["fp8_fp8_fp8+fp16", "fp16_fp16_fp16+fp16", "fp8_fp16_fp32+fp32"])
