@@ -37,8 +37,8 @@ def log(*a):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--regime", default="fp32", help="precision regime of the training state: fp32 (FP32 master weights and "
                     "moments, bf16 compute weights; the default) or one of the low-precision regimes of Sec. 5.6: "
@@ -459,14 +459,18 @@ def main():
         for _ in range(args.warmup):
             one_step(False)
         torch.cuda.synchronize()
+        step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        step_marks[0].record(stream)
+        for n in range(args.steps):
             one_step(True)
+            step_marks[n + 1].record(stream)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
     B.ckpt_plan_device_status(plan, stream)
     ms_per_step = elapsed / args.steps * 1e3
     value = step_bytes / (elapsed / args.steps) / 1e9
+    per_step_ms = sorted(step_marks[n].elapsed_time(step_marks[n + 1]) for n in range(args.steps))
 
     per_kind = {}
     for kind, nbytes, e0, e1 in timings:
@@ -510,6 +514,7 @@ def main():
                    "window": wl.window, "step": "W x snapshot_pack + W x (restore_unpack + convert_replay), HBM-resident",
                    "step_algorithmic_bytes": step_bytes},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "ms_per_step_median": round(per_step_ms[len(per_step_ms) // 2], 3), "ms_per_step_min": round(per_step_ms[0], 3),
         "replay_iters_per_s": round(replay_iters_per_s, 2),
         "kernels": kernels,
         "roofline": roofline,
