@@ -149,8 +149,9 @@ typedef struct {
   uint64_t step;
   const float *d_scales; /* device, [4][n_tensors] kind-major (master, m, v, compute), or NULL = all 1:
                             per-tensor scale s of the kinds stored narrower than FP32, bits = encode(x * s),
-                            x = decode(bits) * (1 / s) in FP32.  Kinds stored as FP32 ignore theirs.  The
-                            array must stay valid until the replay has run. */
+                            x = decode(bits) * (1 / s) in FP32.  Kinds stored as FP32 ignore theirs.  Scales
+                            must be positive and finite (they are not checked: the array lives on the
+                            device).  The array must stay valid until the replay has run. */
 } moev_adam;
 
 typedef struct {
