@@ -336,6 +336,27 @@ int restore_unpack(moev_plan *plan, uint32_t slot, const void *h_pinned, void *d
 int convert_replay(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
                    void *const *grads, const moev_state *state, void *stream);
 
+/* convert_replay_static: convert_replay for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  Same step, same kernels, same results as
+ * convert_replay, but the call allocates, frees and uploads nothing:
+ *   - the plan's device tables must be resident already (ckpt_plan_upload, or any earlier GPU call with the
+ *     same launch knobs); MOEV_E_INVAL otherwise;
+ *   - the tables of pointers are passed ON THE DEVICE and owned by the caller: d_state_table = device array
+ *     [4 * n_tensors] of device pointers, kind-major (all master, all m, all v, all compute), d_grad_table =
+ *     device array [n_tensors] (entries of frozen operators are not read and may be null); both 8-byte aligned,
+ *     every tensor they name 16-byte aligned (not checked: the tables live on the device);
+ *   - the step's scratch (the compacted tile list the kernels hand from one to the other) lives in a static
+ *     device array inside the library, sized for plans of at most MOEV_STATIC_MAX_TENSORS tensors (256 KiB per
+ *     GPU, held from library load until the process ends); larger plans are refused with MOEV_E_RANGE.
+ * All calls on one GPU share that array and each call rewrites the part it uses, so two calls that may run
+ * at the same time on one GPU (different streams, different threads) race: order them.  One-tile-per-workgroup
+ * launch shape only (MOEV_E_INVAL if MOEV_TUNE_PERSISTENT is set).  A null gradient of an active operator is
+ * reported through ckpt_plan_device_status like in convert_replay.
+ * Errors: MOEV_E_INVAL, MOEV_E_RANGE, MOEV_E_HIP. */
+#define MOEV_STATIC_MAX_TENSORS 65536u
+int convert_replay_static(moev_plan *plan, const moev_adam *adam, const uint8_t *d_active_mask,
+                          void *const *d_grad_table, void *const *d_state_table, void *stream);
+
 /* convert_window_step: one step of the conversion loop (Sec. 3.3: load SS_t, then replay iteration
  * t+1), i.e. restore_unpack(slot) followed by convert_replay(adam) with bit-identical results, but
  * fused: the FP32 state of the operators the snapshot activates is read straight from the packed

@@ -31,7 +31,7 @@ EXPORTS = [
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "ckpt_plan_pack_tile_bytes",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
-    "snapshot_pack", "snapshot_drain", "snapshot_drain_range", "snapshot_peek", "restore_unpack", "convert_replay", "convert_window_step",
+    "snapshot_pack", "snapshot_drain", "snapshot_drain_range", "snapshot_peek", "restore_unpack", "convert_replay", "convert_replay_static", "convert_window_step",
     "moev_copy_probe", "moev_arith_selfcheck", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
     "uplog_gc", "uplog_stats",
 ]
@@ -130,6 +130,7 @@ def _load():
     lib.snapshot_peek.argtypes = [vp, u32, vp, C.POINTER(_Header)]
     lib.restore_unpack.argtypes = [vp, u32, vp, vp, C.POINTER(_State), vp, vp]
     lib.convert_replay.argtypes = [vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
+    lib.convert_replay_static.argtypes = [vp, C.POINTER(_Adam), vp, vp, vp, vp]
     lib.convert_window_step.argtypes = [vp, u32, vp, vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
     lib.moev_arith_selfcheck.argtypes = [C.c_int, C.c_float, u32, u64, u64, C.POINTER(u64), vp]
@@ -376,6 +377,14 @@ def convert_replay(plan, lr, beta1, beta2, eps, weight_decay, step: int, d_activ
     g = _ptr_array(grads)
     _check(_lib.convert_replay(plan.handle, C.byref(adam), _addr(d_active_mask), g, C.byref(state.c),
                                _stream(stream)))
+
+
+def convert_replay_static(plan, lr, beta1, beta2, eps, weight_decay, step: int, d_active_mask, d_grad_table,
+                          d_state_table, stream=None, d_scales=None):
+    """d_grad_table / d_state_table: DEVICE arrays of device pointers ([n_tensors] and [4 * n_tensors] kind-major)."""
+    adam = _Adam(lr, beta1, beta2, eps, weight_decay, step, _addr(d_scales))
+    _check(_lib.convert_replay_static(plan.handle, C.byref(adam), _addr(d_active_mask), _addr(d_grad_table),
+                                      _addr(d_state_table), _stream(stream)))
 
 
 def convert_window_step(plan, slot: int, h_pinned, d_packed, lr, beta1, beta2, eps, weight_decay, step: int,

@@ -70,6 +70,36 @@ struct StageSlot {
 
 }  // namespace
 
+// Scratch of convert_replay_static: the compacted tile list of one replay step ([n_tensors + 1] tile numbers),
+// in device memory that exists from the moment the library is loaded, so that the call allocates nothing.
+// Every GPU holds its own copy of the array at its own address.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: kernels and copies are always given the address that call returned.
+static __device__ __align__(256) uint32_t scratch[MOEV_STATIC_MAX_TENSORS + 64];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+uint32_t* g_scratch_ptr[kMaxDevices] = {};  // per device: address of that device's `scratch`
+
+// Address of the current device's scratch array (resolved once per device, with that device current).
+int scratch_of_current_device(uint32_t** out) {
+  int dev = -1;
+  MOEV_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MOEV_E_INVAL, "device %d is beyond the %d devices this library tracks", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    MOEV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(MOEV_E_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = static_cast<uint32_t*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return MOEV_OK;
+}
+
+}  // namespace
+
 struct moev_plan {
   moev::HostPlan host;
   std::mutex mu;
@@ -313,6 +343,12 @@ int upload_locked(moev_plan* pl, hipStream_t s) {
       pl->broken = true;
       return rc;
     }
+  }
+  {
+    // set-up is also where this device's scratch array (convert_replay_static) gets its address resolved
+    uint32_t* unused = nullptr;
+    int rc = scratch_of_current_device(&unused);
+    if (rc != MOEV_OK) return rc;
   }
 
   // (re)build the scan jobs: they depend on the tile sizes, which moev_tune() may change.  An earlier
@@ -559,27 +595,14 @@ int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_acti
   return MOEV_OK;
 }
 
-// fused_slot >= 0: the FP32 state of the tensors that slot activates is read from d_packed
-int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
-                         const moev_state* state, hipStream_t s, int fused_slot, const void* d_packed) {
+// Argument block of one replay step, everything but the tables of state / gradient pointers and the tile list.
+moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask) {
   const auto& h = p->host;
-  int rc = upload_locked(p, s);
-  if (rc != MOEV_OK) return rc;
-  rc = bind_state(p, state, s);
-  if (rc != MOEV_OK) return rc;
-  std::vector<void*> g(grads, grads + h.n_tensors);
-  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s, p->grads_written);
-  if (rc != MOEV_OK) return rc;
-  rc = wait_for_tables(p, s);
-  if (rc != MOEV_OK) return rc;
-
   moev::AdamArgs a{};
   a.tile_start = p->d_tensor_tile_start;
   a.numel = p->d_numel;
   a.op_of_tensor = p->d_op_of_tensor;
   a.mask = d_active_mask;
-  a.ptrs = p->d_state_ptrs;
-  a.grads = p->d_grad_ptrs;
   a.status = p->d_status;
   a.xcd_regions = static_cast<uint32_t>(p->xcd_regions);
   a.n_tensors = h.n_tensors;
@@ -600,27 +623,27 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   const bool ordinary = a.bc1 >= 0x1p-20f && a.bc1 <= 1.0f && a.bc2 >= 0x1p-20f && a.bc2 <= 1.0f && a.eps >= 0.0f &&
                         a.eps <= 0x1p20f;
   a.plain_divide_sqrt = (p->plain_divide_sqrt && ordinary) ? 1u : 0u;
+  return a;
+}
+
+// The two kernels of a one-tile-per-workgroup replay step: the device compacts the tile list to the tensors
+// that are active (mask) and have gradients into d_active_tile_start ([n_tensors + 1], scratch of the step),
+// then the Adam kernel runs over that list with a grid of `bound` workgroups (the host's upper bound on the
+// number of tiles; surplus workgroups exit after one scalar load).
+// fused_slot >= 0: the FP32 state of the tensors that slot activates is read from d_packed.
+int launch_replay_direct(const moev_plan* p, moev::AdamArgs a, const moev_adam* adam, uint32_t* d_active_tile_start,
+                         uint64_t bound, int fused_slot, const void* d_packed, hipStream_t s) {
+  const auto& h = p->host;
   const bool low_precision = !fp32_regime(h);
-  if (p->persistent && !low_precision) {
-    MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
-    return MOEV_OK;
-  }
   // (state in other formats than FP32 / FP32 / FP32 / BF16 has the one-tile-per-workgroup shape only)
   uint32_t threads = static_cast<uint32_t>(p->adam_threads), unroll = static_cast<uint32_t>(p->adam_unroll);
   if (p->persistent) {
     threads = 256;
     unroll = 1;
-    a.tile_elems = threads * 4 * unroll;
     a.lds_entries = 0;
   }
-  // The device compacts the tile list to the tensors that are active (mask) and have gradients;
-  // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles.
-  uint64_t bound = 0;
-  for (uint32_t t = 0; t < h.n_tensors; ++t)
-    if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
-  bound = direct_grid(bound);
-  MOEV_HIP(moev::launch_active_scan(a, p->d_active_tile_start, s));
-  a.tile_start = p->d_active_tile_start;
+  MOEV_HIP(moev::launch_active_scan(a, d_active_tile_start, s));
+  a.tile_start = d_active_tile_start;
   if (fused_slot >= 0) {
     a.src_off = p->d_src_off + 3ull * h.n_tensors * static_cast<uint32_t>(fused_slot);
     a.packed = static_cast<const uint8_t*>(d_packed);
@@ -630,12 +653,40 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   } else if (low_precision) {
     a.scales = adam->d_scales;
     for (int k = 0; k < 4; ++k) a.fmt[k] = h.fmt[k];
-
     MOEV_HIP(moev::launch_adam_lp(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   } else {
     MOEV_HIP(moev::launch_adam_direct(a, static_cast<uint32_t>(bound), threads, unroll, p->nontemporal != 0, s));
   }
   return MOEV_OK;
+}
+
+// fused_slot >= 0: the FP32 state of the tensors that slot activates is read from d_packed
+int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* grads,
+                         const moev_state* state, hipStream_t s, int fused_slot, const void* d_packed) {
+  const auto& h = p->host;
+  int rc = upload_locked(p, s);
+  if (rc != MOEV_OK) return rc;
+  rc = bind_state(p, state, s);
+  if (rc != MOEV_OK) return rc;
+  std::vector<void*> g(grads, grads + h.n_tensors);
+  rc = sync_ptr_table(p, p->grad_cache, p->grad_valid, p->d_grad_ptrs, g, s, p->grads_written);
+  if (rc != MOEV_OK) return rc;
+  rc = wait_for_tables(p, s);
+  if (rc != MOEV_OK) return rc;
+
+  moev::AdamArgs a = adam_args(p, adam, d_active_mask);
+  a.ptrs = p->d_state_ptrs;
+  a.grads = p->d_grad_ptrs;
+  if (p->persistent && fp32_regime(h)) {
+    MOEV_HIP(moev::launch_adam_persistent(a, grid_for(p, p->tensor_tiles, p->adam_max_blocks), p->nontemporal != 0, s));
+    return MOEV_OK;
+  }
+  if (p->persistent) a.tile_elems = 256 * 4;
+  // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles
+  uint64_t bound = 0;
+  for (uint32_t t = 0; t < h.n_tensors; ++t)
+    if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
+  return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound), fused_slot, d_packed, s);
 }
 
 }  // namespace
@@ -1077,6 +1128,50 @@ int convert_replay(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_
   if (rc != MOEV_OK) return rc;
   std::lock_guard<std::mutex> lock(p->mu);
   return launch_replay_locked(p, adam, d_active_mask, grads, state, static_cast<hipStream_t>(stream), -1, nullptr);
+}
+
+int convert_replay_static(moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask, void* const* d_grad_table,
+                          void* const* d_state_table, void* stream) {
+  if (!p || !adam || !d_active_mask || !d_grad_table || !d_state_table)
+    return fail(MOEV_E_INVAL, "convert_replay_static: null argument");
+  const auto& h = p->host;
+  if (h.n_tensors > MOEV_STATIC_MAX_TENSORS)
+    return fail(MOEV_E_RANGE, "convert_replay_static: %u tensors, the static scratch holds the tile list of at most %u",
+                h.n_tensors, static_cast<unsigned>(MOEV_STATIC_MAX_TENSORS));
+  if ((reinterpret_cast<uintptr_t>(d_grad_table) | reinterpret_cast<uintptr_t>(d_state_table)) & 7u)
+    return fail(MOEV_E_INVAL, "convert_replay_static: the pointer tables must be 8-byte aligned");
+  if (adam->step == 0) return fail(MOEV_E_INVAL, "convert_replay_static: step counts from 1");
+  if (!fp32_regime(h)) {
+    if (!moev::lp_formats_supported(h.fmt))
+      return fail(MOEV_E_INVAL, "convert_replay_static: no replay kernel for storage formats %u, %u, %u, %u", h.fmt[0],
+                  h.fmt[1], h.fmt[2], h.fmt[3]);
+    if (!moev::lp_shape_supported(static_cast<uint32_t>(p->adam_threads), static_cast<uint32_t>(p->adam_unroll)))
+      return fail(MOEV_E_INVAL, "convert_replay_static: the low-precision replay runs with 64, 128 or 256 threads and unroll 1 or 2");
+    if (adam->d_scales && (reinterpret_cast<uintptr_t>(adam->d_scales) & 3u))
+      return fail(MOEV_E_INVAL, "convert_replay_static: d_scales is not 4-byte aligned");
+  }
+  std::lock_guard<std::mutex> lock(p->mu);
+  if (p->persistent)
+    return fail(MOEV_E_INVAL, "convert_replay_static: one-tile-per-workgroup launch shape only (MOEV_TUNE_PERSISTENT is set)");
+  if (!p->uploaded || p->broken)
+    return fail(MOEV_E_INVAL, "convert_replay_static: the plan's device tables are not resident; call ckpt_plan_upload "
+                "first (this call allocates and uploads nothing)");
+  int dev = -1;
+  MOEV_HIP(hipGetDevice(&dev));
+  if (dev != p->device) return fail(MOEV_E_INVAL, "plan lives on device %d but device %d is current", p->device, dev);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint32_t* d_scratch = nullptr;
+  int rc = scratch_of_current_device(&d_scratch);  // resolved by ckpt_plan_upload already: a table lookup
+  if (rc != MOEV_OK) return rc;
+  rc = wait_for_tables(p, s);  // the layout scan may have run on another stream
+  if (rc != MOEV_OK) return rc;
+
+  moev::AdamArgs a = adam_args(p, adam, d_active_mask);
+  a.ptrs = d_state_table;
+  a.grads = d_grad_table;
+  // the gradient table lives on the device, so the host cannot tell which entries are null: the grid covers
+  // the tiles of every tensor, and workgroups beyond the step's compacted list exit at once
+  return launch_replay_direct(p, a, adam, d_scratch, direct_grid(p->tensor_tiles), -1, nullptr, s);
 }
 
 int convert_window_step(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_adam* adam,
