@@ -187,21 +187,28 @@ def _gen(device, seed: int) -> torch.Generator:
     return g
 
 
+def make_state_tensor(wl: Workload, kind: str, t: int, seed: int = 0, device="cpu") -> torch.Tensor:
+    """Tensor `t` of one kind of the state make_state() builds, regenerated on its own (same bits): lets a
+    caller whose state does not fit twice compare one tensor at a time."""
+    n = wl.tensors[t][1]
+    src = "master" if kind == "compute" else kind
+    std = 0.02 if src == "master" else 1e-3
+    x = torch.empty(n, dtype=torch.float32, device=device)
+    x.normal_(0.0, std, generator=_gen(device, stream_seed(seed, _STREAM[src], t)))
+    if kind == "v":
+        x.square_()
+    return x.to(torch.bfloat16) if kind == "compute" else x
+
+
 def make_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, List[torch.Tensor]]:
     """master ~ N(0, std 0.02), m ~ N(0, std 1e-3), v = N(0, std 1e-3)^2 (so v >= 0),
     compute = bfloat16 copy of master.  One generator stream per (kind, tensor)."""
     st: Dict[str, List[torch.Tensor]] = {"master": [], "m": [], "v": [], "compute": []}
-    for t, (_, n) in enumerate(wl.tensors):
-        p = torch.empty(n, dtype=torch.float32, device=device)
-        p.normal_(0.0, 0.02, generator=_gen(device, stream_seed(seed, _STREAM["master"], t)))
-        m = torch.empty(n, dtype=torch.float32, device=device)
-        m.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["m"], t)))
-        v = torch.empty(n, dtype=torch.float32, device=device)
-        v.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["v"], t)))
-        v.square_()
+    for t in range(wl.n_tensors):
+        p = make_state_tensor(wl, "master", t, seed, device)
         st["master"].append(p)
-        st["m"].append(m)
-        st["v"].append(v)
+        st["m"].append(make_state_tensor(wl, "m", t, seed, device))
+        st["v"].append(make_state_tensor(wl, "v", t, seed, device))
         st["compute"].append(p.to(torch.bfloat16))
     return st
 

@@ -580,15 +580,18 @@ def _compare_adam(ds, ref, label=""):
     return worst
 
 
+@pytest.mark.parametrize("plain", [1, 0], ids=["plain_divide_sqrt", "full_divide_sqrt"])
 @pytest.mark.parametrize("seed,wd,heavy,adam_tile,blocks,nt,shape", [
     (1, 0.0, False, None, None, 1, None), (2, 0.1, True, None, None, 0, (64, 1)), (3, 0.0, True, None, None, 1, (512, 2)),
     (4, 0.01, False, None, None, 1, (256, 4)), (5, 0.0, False, None, None, 0, (1024, 1)),
     (1, 0.0, False, 8192, None, 1, None), (2, 0.1, True, 1024, 3, 1, None), (3, 0.0, True, 4096, 1, 0, None),
     (4, 0.01, False, 16384, 9, 0, None),
 ])
-def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt, shape):
+def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt, shape, plain):
     """One replayed iteration on ragged tensors with a mixed active/frozen mask: FP32 state within
-    1e-6 relative of the oracle (expected bit-identical), frozen tensors and guards untouched."""
+    1e-6 relative of the oracle (expected bit-identical), frozen tensors and guards untouched.  Both
+    with the plain division / square-root sequences where the operands allow them (the default) and
+    with the compiler's full IEEE sequences everywhere."""
     wl = ragged_workload(40 + seed)
     wl.weight_decay, wl.heavy_tail = wd, heavy
     model, hp = model_of(wl), hp_of(wl)
@@ -596,6 +599,7 @@ def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks
     ds = DeviceState(st_cpu, dev)
     ref = state_of(st_cpu)
     plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt, adam_shape=shape)
+    B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, plain)
     rng = np.random.default_rng(seed)
     mask_np = (rng.random(wl.n_ops) < 0.6).astype(np.uint8)
     mask_np[0] = 1
@@ -615,7 +619,8 @@ def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks
     print(f"adam seed {seed}: worst rel err {worst:.3g}, bit-identical={exact}")
 
 
-def test_adam_special_values(orc, dev):
+@pytest.mark.parametrize("plain", [1, 0], ids=["plain_divide_sqrt", "full_divide_sqrt"])
+def test_adam_special_values(orc, dev, plain):
     """NaN / Inf / denormal / zero inputs propagate exactly as in the oracle (no flushing)."""
     n = 4096 + 3
     wl = W.Workload("special", [(0, n)], [0], 1)
@@ -635,6 +640,7 @@ def test_adam_special_values(orc, dev):
     ds = DeviceState(st_cpu, dev)
     ref = state_of(st_cpu)
     plan = make_plan(wl)
+    B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, plain)
     mask = torch.ones(1, dtype=torch.uint8, device=dev)
     B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, 11, mask, [g.to(dev)], ds.state)
     torch.cuda.synchronize()
