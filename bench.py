@@ -43,7 +43,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--config", default="all", choices=["all", "c0", "c1", "c2", "c3", "c4"],
+                    help="all (default): configs[1] is the headline (the contract's fields describe it) and the line also "
+                         "carries configs[2], configs[3] and configs[4] under `configs`; cN: that workload alone")
+    ap.add_argument("--sub-steps", type=int, default=5, help="timed steps of each workload under `configs` (2 warm-up steps)")
     ap.add_argument("--regime", default="fp32", help="precision regime of the training state: fp32 (FP32 master weights and "
                     "moments, bf16 compute weights; the default) or one of the low-precision regimes of Sec. 5.6: "
                     "fp16_fp16_fp16+fp16, fp8_fp32_fp32+fp32, fp8_fp16_fp32+fp32, fp8_fp16_fp8+fp16, fp8_fp8_fp8+fp16 "
@@ -51,12 +54,17 @@ def parse_args():
     ap.add_argument("--no-drain", action="store_true", help="skip the host-link drain measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--overlap", action="store_true", help="also time the drain under a concurrent bf16 GEMM loop")
-    ap.add_argument("--drain-last-slot", action="store_true", help="configs[3]: overlap/drain measurements on the last slot (19 GB) instead of slot 0 (42 GB)")
+    ap.add_argument("--overlap-slot", type=int, default=-1, help="configs[3]: slot of the overlap / drain measurements; default the "
+                    "last one (19.3 GB, what this box can pin in one piece; slot 0 is 41.9 GB)")
+    ap.add_argument("--cu-mask-sweep", action="store_true", help="configs[3]: also run the pack on side streams restricted to "
+                    "192, 128, 96, 64 and 32 compute units (hipExtStreamCreateWithCUMask) against the GEMM loop")
     ap.add_argument("--persistent", action="store_true", help="fixed-grid launch shape (LDS-staged tile table)")
     ap.add_argument("--copy-tile", type=int, default=0)
     ap.add_argument("--adam-tile", type=int, default=0)
     ap.add_argument("--copy-blocks", type=int, default=0)
     ap.add_argument("--adam-blocks", type=int, default=0)
+    ap.add_argument("--adam-shape", default="", help="one-tile-per-workgroup shape of the replay as THREADSxUNROLL, e.g. 64x2 "
+                    "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-regions", type=int, default=-1)
     ap.add_argument("--plain-divide-sqrt", type=int, default=-1, help="0: always the full IEEE division / square-root sequences in the replay")
@@ -123,82 +131,142 @@ def regime_of(name, torch, W):
     return dtypes, tuple(torch.empty(0, dtype=d).element_size() for d in dtypes)
 
 
-def cpu_baseline(cfg_name, seed, regime="fp32"):
-    """The oracle, as it stands, on a bounded sample of the same workload (single thread)."""
-    import numpy as np
-    import torch
+def _oracle_sample(cfg_name, parts, W):
+    """The bounded sample of a workload the oracle is timed on, cut into `parts` equal shares: every share has all
+    the operators and the whole schedule of the sample and 1/parts of the columns of every tensor."""
+    if cfg_name == "c1":
+        return (W.mixtral_layer(d_ff=14336 // 8 // parts),
+                "configs[1] with d_ff 1792 (1/8 of the columns): 8 experts, W=8, whole window pack+unpack+replay")
+    if cfg_name in ("c2", "c4"):
+        return (W.fine_grained_stack(n_layers=1, n_routed=16, n_shared=2, per_slot=4, d_ff=704 // parts,
+                                     heavy_tail=cfg_name == "c4"),
+                "one layer of 16 routed + 2 shared experts with d_ff 704 (half of the columns), W=4, whole window "
+                "pack+unpack+replay")
+    if cfg_name == "c3":
+        return (W.ep_rank_share(n_layers=1, n_experts=32, d_ff=512 // parts),
+                "one of the 16 layers (32 experts, W=8) with d_ff 512 (1/4 of the columns): W x (pack + unpack), no replay")
+    return W.tiny_moe(d_hidden=1024 // parts), "configs[0], whole window"
+
+
+def _oracle_leg(cfg_name, seed, regime, parts, share, barrier, queue):
+    """One process of an oracle timing leg: the unchanged single-threaded oracle over one share of the sample."""
+    try:
+        import numpy as np
+        import torch
+        if parts > 1:
+            torch.set_num_threads(1)   # input generation only; the oracle itself is single-threaded C
+
+        import oracle
+        from paper_2412_15411_amd import workloads as W
+
+        wl, sample = _oracle_sample(cfg_name, parts, W)
+        if regime != "fp32" and cfg_name == "c1" and parts == 1:   # the oracle converts element by element there
+            wl = W.mixtral_layer(d_ff=14336 // 64)
+            sample = "configs[1] with d_ff 224 (1/64 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
+        seed = seed + 7919 * share
+
+        def np_of(t):
+            if t.element_size() == 2:
+                return t.view(torch.int16).numpy().view(np.uint16)
+            return t.view(torch.uint8).numpy() if t.element_size() == 1 else t.numpy()
+
+        dtypes, widths = regime_of(regime, torch, W)
+        formats = scales = None
+        if dtypes is None:
+            st = W.make_state(wl, seed=seed)
+        else:
+            fmt_of = {torch.float32: oracle.FMT_F32, torch.float16: oracle.FMT_F16, torch.bfloat16: oracle.FMT_BF16,
+                      torch.float8_e4m3fn: oracle.FMT_E4M3, torch.float8_e5m2: oracle.FMT_E5M2}
+            formats = tuple(fmt_of[d] for d in dtypes)
+            per_kind = W.default_scales(dtypes)
+            st = W.make_low_precision_state(wl, dtypes, per_kind, seed=seed)
+            scales = np.ascontiguousarray(np.array([[x] * wl.n_tensors for x in per_kind], dtype=np.float32))
+            sample += f"; state stored as {regime}"
+        state = oracle.State(*[[np_of(t) for t in st[k]] for k in ("master", "m", "v", "compute")])
+        model = oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, 256, widths, formats)
+        hp = oracle.AdamHP(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
+        replay = cfg_name != "c3"
+        grads = [np_of(g) for g in W.make_grads(wl, wl.t0 + 1, seed=seed)] if replay else None
+        snaps = [np.empty(oracle.layout(model, k)[1], dtype=np.uint8) for k in range(wl.window)]
+        for sn in snaps:
+            sn.fill(0)  # touch the pages before timing
+        mask = np.zeros(wl.n_ops, dtype=np.uint8)
+        barrier.wait()
+        t_begin = time.monotonic()
+        t_pack = t_unpack = t_replay = 0.0
+        b_pack = b_unpack = b_replay = 0
+        for k in range(wl.window):
+            t0 = time.monotonic()
+            oracle.pack(model, k, wl.t0 + k, state, out=snaps[k])
+            t_pack += time.monotonic() - t0
+            b_pack += pack_bytes(wl, k, widths)
+        for i in range(wl.window):
+            t0 = time.monotonic()
+            oracle.unpack(model, i, snaps[i], state, mask)
+            t1 = time.monotonic()
+            if replay:
+                oracle.replay_step(model, hp, wl.t0 + i + 1, mask, grads, state, scales)
+                b_replay += replay_bytes(wl, i, widths)
+            t2 = time.monotonic()
+            t_unpack += t1 - t0
+            t_replay += t2 - t1
+            b_unpack += unpack_bytes(wl, i, widths)
+        queue.put({"share": share, "begin": t_begin, "end": time.monotonic(), "sample": sample, "window": wl.window,
+                   "t": (t_pack, t_unpack, t_replay), "b": (b_pack, b_unpack, b_replay)})
+    except BaseException as e:  # the parent must not wait for ever
+        try:
+            barrier.abort()
+        except Exception:
+            pass
+        queue.put({"share": share, "error": repr(e)})
+
+
+def _oracle_legs(cfg_name, seed, regime, parts):
+    """Runs `parts` forked processes (fork: nothing here has touched the GPU yet), each timing the oracle on its
+    share between a common barrier and its own end; returns the aggregate figures."""
+    import multiprocessing as mp
 
     import oracle
-    from paper_2412_15411_amd import workloads as W
-
     oracle.build()
-    if cfg_name == "c1" and regime != "fp32":   # the oracle converts element by element there: a smaller sample
-        wl = W.mixtral_layer(d_ff=14336 // 64)
-        sample = "configs[1] with d_ff 224 (1/64 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
-    elif cfg_name == "c1":
-        wl = W.mixtral_layer(d_ff=14336 // 8)
-        sample = "configs[1] with d_ff 1792 (1/8 of the columns): 8 experts, W=8, whole window pack+unpack+replay"
-    elif cfg_name in ("c2", "c4"):
-        wl = W.fine_grained_stack(n_layers=1, n_routed=16, n_shared=2, per_slot=4, heavy_tail=cfg_name == "c4")
-        sample = "one layer of 16 routed + 2 shared experts at full expert size, W=4, whole window"
-    else:
-        wl = W.tiny_moe()
-        sample = "configs[0], whole window"
+    ctx = mp.get_context("fork")
+    barrier, queue = ctx.Barrier(parts), ctx.Queue()
+    procs = [ctx.Process(target=_oracle_leg, args=(cfg_name, seed, regime, parts, w, barrier, queue)) for w in range(parts)]
+    for pr in procs:
+        pr.start()
+    results = [queue.get(timeout=600) for _ in procs]
+    for pr in procs:
+        pr.join(timeout=60)
+    bad = [r["error"] for r in results if "error" in r]
+    if bad:
+        raise RuntimeError("oracle timing leg failed: " + "; ".join(bad))
+    wall = max(r["end"] for r in results) - min(r["begin"] for r in results)
+    b = [sum(r["b"][k] for r in results) for k in range(3)]
+    # per phase: the bytes of all shares over the longest share's time in that phase
+    t = [max(r["t"][k] for r in results) for k in range(3)]
+    out = {"value": round(sum(b) / wall / 1e9, 3), "unit": "GB/s", "cores": parts, "kind": "oracle",
+           "sample": results[0]["sample"], "seconds": round(wall, 2),
+           "pack_GBs": round(b[0] / t[0] / 1e9, 3), "unpack_GBs": round(b[1] / t[1] / 1e9, 3)}
+    if b[2]:
+        out["replay_GBs"] = round(b[2] / t[2] / 1e9, 3)
+        out["replay_iters_per_s"] = round(results[0]["window"] / t[2], 3)
+    return out
 
-    def np_of(t):
-        if t.element_size() == 2:
-            return t.view(torch.int16).numpy().view(np.uint16)
-        return t.view(torch.uint8).numpy() if t.element_size() == 1 else t.numpy()
 
-    dtypes, widths = regime_of(regime, torch, W)
-    formats = scales = None
-    if dtypes is None:
-        st = W.make_state(wl, seed=seed)
-    else:
-        fmt_of = {torch.float32: oracle.FMT_F32, torch.float16: oracle.FMT_F16, torch.bfloat16: oracle.FMT_BF16,
-                  torch.float8_e4m3fn: oracle.FMT_E4M3, torch.float8_e5m2: oracle.FMT_E5M2}
-        formats = tuple(fmt_of[d] for d in dtypes)
-        per_kind = W.default_scales(dtypes)
-        st = W.make_low_precision_state(wl, dtypes, per_kind, seed=seed)
-        scales = np.ascontiguousarray(np.array([[x] * wl.n_tensors for x in per_kind], dtype=np.float32))
-        sample += f"; state stored as {regime}"
-    state = oracle.State(*[[np_of(t) for t in st[k]] for k in ("master", "m", "v", "compute")])
-    model = oracle.Model(list(wl.tensors), list(wl.order), list(wl.slot_of_op), wl.window, 256, widths, formats)
-    hp = oracle.AdamHP(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
-    grads = [np_of(g) for g in W.make_grads(wl, wl.t0 + 1, seed=seed)]
-    snaps = [np.empty(oracle.layout(model, k)[1], dtype=np.uint8) for k in range(wl.window)]
-    for s in snaps:
-        s.fill(0)  # touch the pages before timing
-    total_bytes = 0
-    t_begin = time.perf_counter()
-    for k in range(wl.window):
-        oracle.pack(model, k, wl.t0 + k, state, out=snaps[k])
-        total_bytes += pack_bytes(wl, k, widths)
-    t_pack = time.perf_counter()
-    mask = np.zeros(wl.n_ops, dtype=np.uint8)
-    t_unpack = t_replay = 0.0
-    for i in range(wl.window):
-        t0 = time.perf_counter()
-        oracle.unpack(model, i, snaps[i], state, mask)
-        t1 = time.perf_counter()
-        oracle.replay_step(model, hp, wl.t0 + i + 1, mask, grads, state, scales)
-        t2 = time.perf_counter()
-        t_unpack += t1 - t0
-        t_replay += t2 - t1
-        total_bytes += unpack_bytes(wl, i, widths) + replay_bytes(wl, i, widths)
-    elapsed = time.perf_counter() - t_begin
-    return {
-        "value": round(total_bytes / elapsed / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": sample, "seconds": round(elapsed, 2),
-        "pack_GBs": round(sum(pack_bytes(wl, k, widths) for k in range(wl.window)) / (t_pack - t_begin) / 1e9, 3),
-        "unpack_GBs": round(sum(unpack_bytes(wl, k, widths) for k in range(wl.window)) / t_unpack / 1e9, 3),
-        "replay_GBs": round(sum(replay_bytes(wl, k, widths) for k in range(wl.window)) / t_replay / 1e9, 3),
-        "replay_iters_per_s": round(wl.window / t_replay, 3),
-    }
+def cpu_baseline(cfg_name, seed, regime="fp32"):
+    """The oracle, as it stands, on a bounded sample of the same workload: (i) single-threaded, on one core;
+    (ii) the same unchanged code in one process per host core (at most 16, this box's share), each on an equal
+    share of the sample's columns, started together.  Must be called before the process touches the GPU."""
+    single = _oracle_legs(cfg_name, seed, regime, 1)
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    if cores > 1:
+        every = _oracle_legs(cfg_name, seed, regime, cores)
+        every["sample"] = f"the same sample, {cores} processes, each the unchanged oracle on 1/{cores} of the columns of every tensor"
+        single["all_cores"] = every
+    return single
 
 
 # ---------------------------------------------------------------------------------------
-def rank_share_bench(args, torch, B, W, dev):
+def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     """configs[3]: one GPU's share of a large MoE (180 GB of state resident in HBM).  The packed
     snapshots of a window (245 GB) cannot be resident next to the state, so a step here is
     W x (snapshot_pack into one reused buffer, restore_unpack from it); the replay is not part of
@@ -235,11 +303,11 @@ def rank_share_bench(args, torch, B, W, dev):
             timed("unpack", unpack_bytes(wl, k), lambda: B.restore_unpack(plan, k, None, packed, state, mask, stream=main), record, main)
 
     step_bytes = sum(pack_bytes(wl, k) + unpack_bytes(wl, k) for k in range(wl.window))
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         one_step(True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -256,10 +324,10 @@ def rank_share_bench(args, torch, B, W, dev):
         kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                          "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
                          "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
-    value = step_bytes / (elapsed / args.steps) / 1e9
+    value = step_bytes / (elapsed / steps) / 1e9
     out = {
-        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True,
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"configs[3] {wl.name}", "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
                    "step": "W x (snapshot_pack + restore_unpack) through one reused packed buffer, HBM-resident; no replay",
@@ -270,7 +338,7 @@ def rank_share_bench(args, torch, B, W, dev):
     }
 
     # ---- overlap: pack and drain of slot `k` against a bf16 GEMM loop on the main stream -------
-    k = wl.window - 1 if args.drain_last_slot else 0
+    k = args.overlap_slot if 0 <= args.overlap_slot < wl.window else wl.window - 1
     nbytes = B.ckpt_plan_packed_bytes(plan, k)
     a = torch.randn(8192, 4096, dtype=torch.bfloat16, device=dev)
     b = torch.randn(4096, 2048, dtype=torch.bfloat16, device=dev)
@@ -294,7 +362,7 @@ def rank_share_bench(args, torch, B, W, dev):
 
     def pack_on_side(p):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(side)
+        e0.record(side)          # `side` is looked up at call time (the CU-mask sweep rebinds it)
         B.snapshot_pack(p, k, wl.t0 + k, state, packed, stream=side)
         e1.record(side)
         return e0, e1
@@ -302,8 +370,7 @@ def rank_share_bench(args, torch, B, W, dev):
     # the default shape floods the dispatcher with small workgroups; the fixed-grid shape with a cap
     # on its workgroups leaves compute units to the GEMM
     overlap = []
-    for label, cap in (("one tile per workgroup (default)", None), ("fixed grid, 2048 workgroups", 2048),
-                       ("fixed grid, 1024 workgroups", 1024), ("fixed grid, 512 workgroups", 512),
+    for label, cap in (("one tile per workgroup (default)", None), ("fixed grid, 1024 workgroups", 1024),
                        ("fixed grid, 256 workgroups", 256)):
         p = plan
         if cap is not None:
@@ -333,6 +400,42 @@ def rank_share_bench(args, torch, B, W, dev):
     out["pack_under_gemm"] = {"slot": k, "gemm": "bf16 [8192x4096]x[4096x2048] back to back on the main stream",
                               "gemm_TFLOPs_alone": round(gemm_tflops, 1), "runs": overlap}
 
+    # The same pack (default shape) on a side stream that may only use the first n compute units: does leaving
+    # compute units to the GEMM reduce what the GEMM loses?
+    if args.cu_mask_sweep:
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32)]
+        hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+        default_side, masked = side, []
+        for n_cu in (192, 128, 96, 64, 32):
+            words = (ctypes.c_uint32 * 8)(*[(1 << min(32, max(0, n_cu - 32 * w))) - 1 for w in range(8)])
+            raw = ctypes.c_void_p()
+            rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(raw), 8, words)
+            if rc != 0:
+                masked.append({"compute_units": n_cu, "error": f"hipExtStreamCreateWithCUMask returned {rc}"})
+                continue
+            side = torch.cuda.ExternalStream(raw.value)     # pack_on_side() launches on `side`
+            pack_on_side(plan)
+            torch.cuda.synchronize()
+            p0, p1 = pack_on_side(plan)
+            torch.cuda.synchronize()
+            pack_alone_ms = p0.elapsed_time(p1)
+            n_gemm = max(50, int(3 * pack_alone_ms / per_gemm_ms))
+            g0, g1 = gemm_loop(n_gemm)
+            torch.cuda.synchronize()
+            gemm_alone_ms = g0.elapsed_time(g1)
+            g0, g1 = gemm_loop(n_gemm)
+            p0, p1 = pack_on_side(plan)
+            torch.cuda.synchronize()
+            masked.append({"compute_units": n_cu, "n_gemm": n_gemm, "pack_ms_alone": round(pack_alone_ms, 3),
+                           "pack_GBs_alone": round(pack_bytes(wl, k) / (pack_alone_ms / 1e3) / 1e9, 1),
+                           "pack_ms_with_gemm": round(p0.elapsed_time(p1), 3), "gemm_ms_alone": round(gemm_alone_ms, 3),
+                           "gemm_ms_lost": round(g0.elapsed_time(g1) - gemm_alone_ms, 3)})
+            side = default_side
+            hip.hipStreamDestroy(raw)
+        out["pack_under_gemm"]["cu_masked_side_stream"] = masked
+
     if not args.no_drain:
         t_pin = time.time()
         host = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
@@ -350,48 +453,53 @@ def rank_share_bench(args, torch, B, W, dev):
         g0, g1 = gemm_loop(n_gemm)
         torch.cuda.synchronize()
         gemm_alone_ms = g0.elapsed_time(g1)
-        g0, g1 = gemm_loop(n_gemm)
+        # the GEMM loop again with the drain on the side stream; events after every 1/12 of the loop put both on one
+        # time axis (milliseconds since the loop's start)
+        batch = max(1, n_gemm // 12)
+        marks = []
+        origin = torch.cuda.Event(enable_timing=True)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(side)
-        B.snapshot_drain(plan, k, packed, host, side_stream=side)
-        e1.record(side)
+        with torch.cuda.stream(main):
+            origin.record(main)
+            side.wait_event(origin)
+            e0.record(side)
+            B.snapshot_drain(plan, k, packed, host, side_stream=side)
+            e1.record(side)
+            for i in range(n_gemm):
+                torch.mm(a, b, out=c)
+                if (i + 1) % batch == 0 or i + 1 == n_gemm:
+                    ev = torch.cuda.Event(enable_timing=True)
+                    ev.record(main)
+                    marks.append((i + 1, ev))
         torch.cuda.synchronize()
+        t_drain = (origin.elapsed_time(e0), origin.elapsed_time(e1))
+        ends = [(n, origin.elapsed_time(ev)) for n, ev in marks]
+        during = [(n, t) for n, t in ends if t_drain[0] <= t <= t_drain[1]]
         out["drain"] = {"bound": "host-link", "slot": k, "bytes": nbytes, "ms": round(drain_alone_ms, 2),
                         "GBs": round(nbytes / (drain_alone_ms / 1e3) / 1e9, 2),
                         "header_ok": B.snapshot_peek(plan, k, host)["slot"] == k}
         out["drain_under_gemm"] = {
             "gemm": "bf16 [8192x4096]x[4096x2048], %d back to back on the main stream" % n_gemm,
-            "drain_ms": round(e0.elapsed_time(e1), 2), "drain_GBs": round(nbytes / (e0.elapsed_time(e1) / 1e3) / 1e9, 2),
-            "gemm_ms_alone": round(gemm_alone_ms, 2), "gemm_ms_with_drain": round(g0.elapsed_time(g1), 2)}
+            "drain_ms": round(t_drain[1] - t_drain[0], 2),
+            "drain_GBs": round(nbytes / ((t_drain[1] - t_drain[0]) / 1e3) / 1e9, 2),
+            "gemm_ms_alone": round(gemm_alone_ms, 2), "gemm_ms_with_drain": round(ends[-1][1], 2),
+            "gemm_us_per_kernel_alone": round(gemm_alone_ms / n_gemm * 1e3, 2),
+            "gemm_us_per_kernel_while_draining": (round((during[-1][1] - during[0][1]) / (during[-1][0] - during[0][0]) * 1e3, 2)
+                                                  if len(during) > 1 else None),
+            "timeline_ms": {"drain_start": round(t_drain[0], 2), "drain_end": round(t_drain[1], 2),
+                            "gemm_kernels_done_at": [[n, round(t, 2)] for n, t in ends]}}
         del host
-    print(json.dumps(out), flush=True)
+    del st, state, packed, a, b, c
+    return out
 
 
 # ---------------------------------------------------------------------------------------
-def main():
-    args = parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (each expert-parallel rank snapshots and converts its own "
-              "experts independently; there is nothing to exchange). Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2412_15411_amd import binding as B
-    from paper_2412_15411_amd import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
+def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
+    """One workload with a replay (configs[0], [1], [2], [4]): W x snapshot_pack, then W x (restore_unpack +
+    convert_replay), everything resident in HBM.  extras: also the copy probe, the drain, the upstream-log ring and
+    the what-if (the headline workload); otherwise the step, its kernels and the fused conversion only."""
     dtypes, widths = regime_of(args.regime, torch, W)
-    if args.config == "c3":
-        if dtypes is not None:
-            print("bench.py: --config c3 runs in the fp32 regime only", file=sys.stderr)
-            sys.exit(2)
-        return rank_share_bench(args, torch, B, W, dev)
-    wl = W.CONFIGS[args.config]()
+    wl = W.CONFIGS[cfg]()
     t_setup = time.time()
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
     formats, d_scales = (0, 0, 0, 0), None
@@ -419,6 +527,11 @@ def main():
                       (B.TUNE_COPY_MAX_BLOCKS, args.copy_blocks), (B.TUNE_ADAM_MAX_BLOCKS, args.adam_blocks)):
         if val:
             B.moev_tune(plan, knob, val)
+    if args.adam_shape:
+        threads, unroll = (int(x) for x in args.adam_shape.split("x"))
+        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, 1)
+        B.moev_tune(plan, B.TUNE_ADAM_THREADS, threads)
+        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, unroll)
     if args.nontemporal >= 0:
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
     if args.xcd_regions >= 0:
@@ -460,21 +573,21 @@ def main():
     step_bytes = sum(pack_bytes(wl, k, widths) + unpack_bytes(wl, k, widths) + replay_bytes(wl, k, widths)
                      for k in range(wl.window))
     with torch.cuda.stream(stream):
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             one_step(False)
         torch.cuda.synchronize()
-        step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
         step_marks[0].record(stream)
-        for n in range(args.steps):
+        for n in range(steps):
             one_step(True)
             step_marks[n + 1].record(stream)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
     B.ckpt_plan_device_status(plan, stream)
-    ms_per_step = elapsed / args.steps * 1e3
-    value = step_bytes / (elapsed / args.steps) / 1e9
-    per_step_ms = sorted(step_marks[n].elapsed_time(step_marks[n + 1]) for n in range(args.steps))
+    ms_per_step = elapsed / steps * 1e3
+    value = step_bytes / (elapsed / steps) / 1e9
+    per_step_ms = sorted(step_marks[n].elapsed_time(step_marks[n + 1]) for n in range(steps))
 
     per_kind = {}
     for kind, nbytes, e0, e1 in timings:
@@ -495,12 +608,12 @@ def main():
         kname = "k_adam_lp"
     roofline = {"bound": "hbm", "kernel": kname, "achieved": kernels[dominant]["GBs"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": kernels[dominant]["frac_hbm_peak"],
-                "traffic": read_traffic(kname, args.config if dtypes is None else args.config + ":" + args.regime)}
+                "traffic": read_traffic(kname, cfg if dtypes is None else cfg + ":" + args.regime)}
     # The replay of state stored in 1-byte formats moves so few bytes per parameter that the vector ALU, not HBM,
     # bounds it (three correctly rounded divisions and a square root per parameter): then the roofline is the ALU's.
     valu_per_param = read_valu_count("k_adam_lp", args.regime) if dtypes is not None else None
     if kname == "k_adam_lp" and valu_per_param:
-        params_per_s = sum(wl.active_params_at(i) for i in range(wl.window)) * args.steps / (per_kind["replay"]["ms"] / 1e3)
+        params_per_s = sum(wl.active_params_at(i) for i in range(wl.window)) * steps / (per_kind["replay"]["ms"] / 1e3)
         valu_gops = valu_per_param * params_per_s / 1e9
         if valu_gops / VALU_PEAK_GOPS > roofline["frac"]:
             roofline = {"bound": "alu", "kernel": kname, "achieved": round(valu_gops, 1), "peak": VALU_PEAK_GOPS,
@@ -510,10 +623,10 @@ def main():
     replay_iters_per_s = per_kind["replay"]["launches"] / (per_kind["replay"]["ms"] / 1e3)
 
     out = {
-        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config[1]}] {wl.name}", "regime": args.regime, "element_bytes": list(widths),
+        "config": {"workload": f"configs[{cfg[1]}] {wl.name}", "regime": args.regime, "element_bytes": list(widths),
                    "n_ops": wl.n_ops, "n_params": wl.n_params,
                    "window": wl.window, "step": "W x snapshot_pack + W x (restore_unpack + convert_replay), HBM-resident",
                    "step_algorithmic_bytes": step_bytes},
@@ -541,13 +654,13 @@ def main():
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            for _ in range(args.steps):
+            for _ in range(steps):
                 fused_window()
             e1.record(stream)
             torch.cuda.synchronize()
         B.ckpt_plan_device_status(plan, stream)
-        fused_ms = e0.elapsed_time(e1) / args.steps
-        two_call_ms = (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / args.steps
+        fused_ms = e0.elapsed_time(e1) / steps
+        two_call_ms = (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / steps
         return {
             "call": "convert_window_step (restore_unpack + convert_replay in one pass, same results)",
             "ms_per_window": round(fused_ms, 3), "two_call_ms_per_window": round(two_call_ms, 3),
@@ -560,7 +673,7 @@ def main():
     # ---- launch-bound windows: the same step replayed from a HIP graph -------------------------------------
     # (with resident tables every call enqueues kernels only; all gradient pointers are passed in every
     # iteration so that the pointer table stays the same)
-    if args.config == "c0":
+    if cfg == "c0":
         all_grads = W.make_grads(wl, wl.t0 + 1, seed=args.seed, device=dev)
 
         def whole_step():
@@ -578,7 +691,7 @@ def main():
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
                 whole_step()
-            reps = max(args.steps, 20)
+            reps = max(steps, 20)
             e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             e0.record(stream)
             for _ in range(reps):
@@ -592,6 +705,10 @@ def main():
         out["graph_replay"] = {"what": "the whole step (W packs, W x (unpack + replay)) captured once in a HIP graph",
                                "kernels_per_step": 4 * wl.window + 1, "eager_us_per_step": round(e0.elapsed_time(e1) / reps * 1e3, 1),
                                "graph_us_per_step": round(e1.elapsed_time(e2) / reps * 1e3, 1)}
+
+    if not extras:
+        del state, st, grads, packed
+        return out
 
     # ---- plain contiguous copy of known size: the box's practical copy ceiling, and the kernel
     # against which the rocprofv3 HBM counters are calibrated ----------------------------------
@@ -712,7 +829,7 @@ def main():
         link = out["drain"]["GBs"] * 1e9
         stall_s = max(e0.elapsed_time(e1) for kind, _, e0, e1 in timings if kind == "pack") / 1e3
         convert_s = (out["fused_conversion"]["ms_per_window"] if "fused_conversion" in out else
-                     (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / args.steps) / 1e3
+                     (per_kind["unpack"]["ms"] + per_kind["replay"]["ms"]) / steps) / 1e3
         rows = []
         for t_iter in (0.25, 0.5, 1.0, 2.0):
             w, a = B.moev_find_window_size(wl.n_ops, t_iter, widths[3] * per_op, widths[0] * per_op,
@@ -728,9 +845,67 @@ def main():
                                   "(expected) / 2 W T_iter (worst) plus the measured conversion; ETTR with a snapshot every iteration",
                           "rows": rows}
 
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, args.seed, args.regime)
+    del state, st, grads, packed
+    return out
 
+
+# ---------------------------------------------------------------------------------------
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (each expert-parallel rank snapshots and converts its own "
+              "experts independently; there is nothing to exchange). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    todo = ["c1", "c2", "c3", "c4"] if args.config == "all" else [args.config]
+    if args.regime != "fp32" and "c3" in todo:
+        if args.config == "c3":
+            print("bench.py: --config c3 runs in the fp32 regime only", file=sys.stderr)
+            sys.exit(2)
+        todo.remove("c3")
+
+    # The oracle's CPU legs run FIRST: their worker processes are forked before anything touches the GPU.
+    cpu = {}
+    if not args.no_cpu_baseline:
+        for cfg in todo:
+            t0 = time.time()
+            cpu[cfg] = cpu_baseline(cfg, args.seed, args.regime)
+            log(f"[bench] oracle legs of {cfg}: {time.time() - t0:.1f} s")
+
+    import torch
+    from paper_2412_15411_amd import binding as B
+    from paper_2412_15411_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    regime_of(args.regime, torch, W)   # exits on an unknown regime
+
+    def run(cfg, steps, warmup, extras):
+        if cfg == "c3":
+            res = rank_share_bench(args, steps, warmup, torch, B, W, dev)
+        else:
+            res = window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev)
+        if cfg in cpu:
+            res["cpu_baseline"] = cpu[cfg]
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        return res
+
+    out = run(todo[0], args.steps, args.warmup, True)
+    if args.config == "all":
+        # the other workloads, timed by the same run: each entry is a complete result of its own
+        # (its step, kernels, roofline; configs[3] also the overlap with compute and the drain)
+        out["configs"] = {}
+        for cfg in todo[1:]:
+            t0 = time.time()
+            sub = run(cfg, args.sub_steps, 2, False)
+            for key in ("metric", "n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
+                sub.pop(key, None)
+            out["configs"][cfg] = sub
+            log(f"[bench] {cfg} done in {time.time() - t0:.1f} s")
     print(json.dumps(out), flush=True)
 
 
