@@ -32,7 +32,9 @@
  *     on another stream waits for that write.  The pointer tables are shared by all calls on a
  *     plan: a call that passes DIFFERENT state or gradient pointers than the previous one rewrites
  *     them, so it must not be enqueued while a kernel of that plan may still run on ANOTHER
- *     stream (order the streams, or use one plan per concurrently processed state).
+ *     stream (order the streams, or use one plan per concurrently processed state).  Replay
+ *     steps (convert_replay, convert_window_step) of ONE plan must be stream-ordered among
+ *     themselves even with unchanged pointers: every step rewrites the plan's list of active tiles.
  *   - HIP graphs: a call whose tables are resident (same plan settings, same state and gradient
  *     pointers as an earlier call) enqueues kernels only and may be captured into a graph; pass
  *     every gradient pointer in every iteration (frozen operators' entries are not read) so that
@@ -52,8 +54,11 @@
  *   offsets: first segment at roundup(256, align); each next one roundup(nbytes, align)
  *           further; padding bytes are zero.
  *   plan hash: 64-bit FNV-1a over u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 element
- *           widths (master, m, v, compute), per tensor (u32 op, u64 numel), per operator
- *           u32 slot, per position u32 order.
+ *           widths (master, m, v, compute), u8 storage formats (MOEV_FMT_* of master, m, v,
+ *           compute, after the defaults by width have been filled in), per tensor (u32 op,
+ *           u64 numel), per operator u32 slot, per position u32 order.  A snapshot therefore
+ *           loads only into a plan with the same operators, schedule, alignment and precision
+ *           regime.
  */
 #ifndef MOEV_H
 #define MOEV_H
@@ -231,6 +236,10 @@ int moev_popularity_capacity_aware(uint32_t n_ops, const double *popularity, con
 double moev_ettr(double t_ckpt_s, double t_iter_s, double ckpt_interval_iters, double expected_recovery_s,
                  double mtbf_s);
 int moev_recovery_time(int sparse, double interval_or_window, double t_iter_s, double *expected_s, double *worst_s);
+
+/* The two bias corrections 1 - beta^step of the replayed Adam step, exactly as convert_replay passes them to
+ * its kernel: evaluated in double precision, rounded to FP32 once.  MOEV_E_INVAL on null pointers or step 0. */
+int moev_bias_corrections(float beta1, float beta2, uint64_t step, float *bc1, float *bc2);
 
 /* queries (host) */
 uint32_t ckpt_plan_window(const moev_plan *plan);

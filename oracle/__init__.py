@@ -55,7 +55,7 @@ class _Segment(C.Structure):
 class _Model(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_tensors", C.c_uint32), ("tensors", C.POINTER(_Tensor)),
                 ("order", C.POINTER(C.c_uint32)), ("slot_of_op", C.POINTER(C.c_uint32)),
-                ("window", C.c_uint32), ("align", C.c_uint32), ("width", _Widths)]
+                ("window", C.c_uint32), ("align", C.c_uint32), ("width", _Widths), ("fmt", C.c_uint32 * 4)]
 
 
 class _State(C.Structure):
@@ -77,6 +77,8 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_layout.restype = C.c_int64
         _lib.orc_plan_hash.restype = C.c_uint64
+        _lib.orc_fnv1a64.restype = C.c_uint64
+        _lib.orc_fnv1a64.argtypes = [C.c_char_p, C.c_uint64]
         _lib.orc_bf16_rne.restype = C.c_uint16
         _lib.orc_bf16_rne.argtypes = [C.c_float]
         _lib.orc_adam_tensor.restype = None
@@ -130,7 +132,8 @@ class Model:
         w = tuple(int(x) for x in self.widths)
         if len(w) == 3:  # (master, both moments, compute)
             w = (w[0], w[1], w[1], w[2])
-        return _Model(self.n_ops, self.n_tensors, ts, order, slots, int(self.window), int(self.align), _Widths(*w))
+        fmt = (C.c_uint32 * 4)(*(self.formats if self.formats is not None else (0, 0, 0, 0)))
+        return _Model(self.n_ops, self.n_tensors, ts, order, slots, int(self.window), int(self.align), _Widths(*w), fmt)
 
 
 @dataclass
@@ -250,6 +253,10 @@ def recovery(kind, interval_or_window, t_iter):
 # --------------------------------------------------------------------------------------
 # layout / pack / unpack
 # --------------------------------------------------------------------------------------
+def fnv1a64(data: bytes) -> int:
+    return lib().orc_fnv1a64(data, C.c_uint64(len(data)))
+
+
 def plan_hash(model: Model) -> int:
     cm = model.c()
     return lib().orc_plan_hash(C.byref(cm))

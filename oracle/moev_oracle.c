@@ -15,48 +15,46 @@
  * =================================================================================== */
 
 /*
- * FindWindowSize (Algorithm 1).  All operators start active; operators are moved to the
- * frozen side one at a time until the estimated transfer time of one snapshot,
- *     ((S_Master + S_Optim) * O_Active + S_Compute * O_Frozen) / B_PCIe,
- * fits inside T_Iter.  The search never goes below two active operators (the loop guard
- * of the listing) and, when it stops at that floor, does not test the fit again.
- * W_sparse = ceil(O_Total / O_Active).
+ * Window size (Sec. 3.5, FindWindowSize of Algorithm 1).  A snapshot that checkpoints `a` of the
+ * O_Total operators with full state carries (S_Master + S_Optim) * a + S_Compute * (O_Total - a)
+ * bytes and must cross the host link within one iteration.  The method wants the SMALLEST window,
+ * i.e. the LARGEST such `a`; it considers a = O_Total, O_Total - 1, ..., 3 and, when none of them
+ * fits, settles for two operators per slot without asking whether two fit (all of them when
+ * there are fewer than three).  W_sparse = ceil(O_Total / O_Active).
  */
+static int snapshot_fits(uint32_t o_total, uint32_t a, double t_iter, double s_compute, double s_master,
+                         double s_optim, double b_pcie) {
+  double bytes = (s_master + s_optim) * (double)a + s_compute * (double)(o_total - a);
+  return bytes / b_pcie <= t_iter;
+}
+
 int orc_find_window_size(uint32_t o_total, double t_iter, double s_compute, double s_master,
                          double s_optim, double b_pcie, uint32_t *w_sparse, uint32_t *o_active) {
   if (o_total == 0 || !w_sparse || !o_active || !(b_pcie > 0.0)) return ORC_BAD_ARG;
-  uint32_t act = o_total;
-  while (act > 2) {
-    uint32_t frozen = o_total - act;
-    double ckpt_size = (s_master + s_optim) * (double)act + s_compute * (double)frozen;
-    if (ckpt_size / b_pcie <= t_iter) break;
-    act -= 1;
-  }
-  *o_active = act;
-  *w_sparse = (o_total + act - 1) / act;
+  uint32_t best = o_total < 2 ? o_total : 2;            /* the floor, taken unchecked */
+  for (uint32_t a = 3; a <= o_total; ++a)               /* every candidate; the largest fitting one wins */
+    if (snapshot_fits(o_total, a, t_iter, s_compute, s_master, s_optim, b_pcie)) best = a;
+  *o_active = best;
+  *w_sparse = o_total / best + (o_total % best != 0);
   return ORC_OK;
 }
 
 /*
- * GenerateSchedule (Algorithm 1).  Slot i of the window holds, as active operators, the
- * i-th run of O_Active consecutive entries of O_Ordered (the last run may be shorter);
- * everything after that run in O_Ordered is that slot's frozen set.  Stored here as the
- * slot index in which each operator is active: the active set of slot i is
- * {e : slot_of_op[e] == i}, its frozen set {e : slot_of_op[e] > i}.
+ * Schedule (Sec. 3.5, GenerateSchedule of Algorithm 1).  O_Ordered is cut into consecutive runs
+ * of O_Active operators, one run per slot, the last run possibly shorter: the operator at
+ * position j of O_Ordered is checkpointed with full state in slot floor(j / O_Active).  A slot's
+ * frozen set is everything behind its run in O_Ordered, i.e. the operators of later slots.
+ * Stored as the slot of every operator: active set of slot i = {e : slot_of_op[e] == i},
+ * frozen set = {e : slot_of_op[e] > i}.
  */
 int orc_generate_schedule(uint32_t n_ops, const uint32_t *order, uint32_t o_active,
                           uint32_t *slot_of_op, uint32_t *w_sparse) {
   if (n_ops == 0 || o_active == 0 || !order || !slot_of_op || !w_sparse) return ORC_BAD_ARG;
-  uint32_t w = (n_ops + o_active - 1) / o_active;
-  for (uint32_t i = 0; i < w; ++i) {
-    uint32_t start = i * o_active;
-    uint32_t end = start + o_active < n_ops ? start + o_active : n_ops;
-    for (uint32_t j = start; j < end; ++j) {
-      if (order[j] >= n_ops) return ORC_BAD_ARG;
-      slot_of_op[order[j]] = i;
-    }
+  for (uint32_t j = 0; j < n_ops; ++j) {
+    if (order[j] >= n_ops) return ORC_BAD_ARG;
+    slot_of_op[order[j]] = j / o_active;
   }
-  *w_sparse = w;
+  *w_sparse = (n_ops - 1) / o_active + 1;
   return ORC_OK;
 }
 
@@ -183,12 +181,32 @@ static uint64_t fnv1a(uint64_t h, uint64_t value, int nbytes) {
 }
 
 /*
- * Identity of a plan, stored in every snapshot header so that a snapshot is never loaded
- * into a model or schedule it was not taken from.  64-bit FNV-1a over the little-endian
- * stream: u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 widths (master, m, v,
- * compute), then per tensor (u32 op, u64 numel), per operator u32 slot, per position
- * u32 order.
+ * Storage format of a kind when the model names none: by element width, 4 bytes = FP32,
+ * 2 bytes = FP16 (bfloat16 for the compute weights), 1 byte = E4M3, anything else = 0 (the kind
+ * is only ever copied).
  */
+static uint32_t storage_format_of_kind(const orc_model *mdl, int kind) {
+  const uint32_t width[4] = {mdl->width.master, mdl->width.m, mdl->width.v, mdl->width.compute};
+  if (mdl->fmt[kind]) return mdl->fmt[kind];
+  if (width[kind] == 4) return ORC_FMT_F32;
+  if (width[kind] == 2) return kind == ORC_COMPUTE ? ORC_FMT_BF16 : ORC_FMT_F16;
+  if (width[kind] == 1) return ORC_FMT_E4M3;
+  return 0;
+}
+
+/*
+ * Identity of a plan, stored in every snapshot header so that a snapshot is never loaded
+ * into a model, schedule or precision regime it was not taken from.  64-bit FNV-1a over the
+ * little-endian stream: u32 n_ops, u32 n_tensors, u32 window, u32 align, u8 widths (master, m,
+ * v, compute), u8 storage formats (master, m, v, compute), then per tensor (u32 op, u64 numel),
+ * per operator u32 slot, per position u32 order.
+ */
+uint64_t orc_fnv1a64(const void *bytes, uint64_t n) {
+  uint64_t h = 0xcbf29ce484222325ull;
+  for (uint64_t i = 0; i < n; ++i) h = fnv1a(h, ((const uint8_t *)bytes)[i], 1);
+  return h;
+}
+
 uint64_t orc_plan_hash(const orc_model *mdl) {
   uint64_t h = 0xcbf29ce484222325ull;
   h = fnv1a(h, mdl->n_ops, 4);
@@ -199,6 +217,7 @@ uint64_t orc_plan_hash(const orc_model *mdl) {
   h = fnv1a(h, mdl->width.m, 1);
   h = fnv1a(h, mdl->width.v, 1);
   h = fnv1a(h, mdl->width.compute, 1);
+  for (int kind = 0; kind < 4; ++kind) h = fnv1a(h, storage_format_of_kind(mdl, kind), 1);
   for (uint32_t t = 0; t < mdl->n_tensors; ++t) {
     h = fnv1a(h, mdl->tensors[t].op, 4);
     h = fnv1a(h, mdl->tensors[t].numel, 8);

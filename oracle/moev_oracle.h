@@ -61,6 +61,7 @@ typedef struct {
   uint32_t window;            /* W_sparse */
   uint32_t align;             /* segment alignment in the packed snapshot */
   orc_widths width;
+  uint32_t fmt[4];            /* ORC_FMT_* of master, m, v, compute; 0 = by element width */
 } orc_model;
 
 /* dense training state, one host pointer per tensor and kind */
@@ -93,6 +94,7 @@ void orc_recovery_dense(double ckpt_interval, double t_iter, double *expected, d
 void orc_recovery_sparse(double w_sparse, double t_iter, double *expected, double *worst);
 
 /* ---- snapshot layout, pack, unpack (Sec. 3.2, Sec. 3.3) ---------------------------- */
+uint64_t orc_fnv1a64(const void *bytes, uint64_t n);   /* the hash function itself, over a byte string */
 uint64_t orc_plan_hash(const orc_model *mdl);
 int64_t orc_layout(const orc_model *mdl, uint32_t slot, orc_segment *segs, uint64_t seg_cap,
                    uint64_t *packed_bytes);

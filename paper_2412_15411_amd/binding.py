@@ -26,7 +26,7 @@ HEADER_BYTES = 256
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",
     "moev_reorder_needed", "moev_popularity_time_decayed", "moev_popularity_capacity_aware", "moev_ettr",
-    "moev_recovery_time", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
+    "moev_recovery_time", "moev_bias_corrections", "ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active",
     "ckpt_plan_hash", "ckpt_plan_width", "ckpt_plan_format", "ckpt_plan_slot_of_op", "ckpt_plan_order", "ckpt_plan_packed_bytes",
     "ckpt_plan_max_packed_bytes", "ckpt_plan_n_segments", "ckpt_plan_segments", "ckpt_plan_active_params",
     "ckpt_plan_pack_tile_bytes",
@@ -96,6 +96,7 @@ def _load():
     lib.moev_ettr.argtypes = [C.c_double] * 5
     lib.moev_ettr.restype = C.c_double
     lib.moev_recovery_time.argtypes = [C.c_int, C.c_double, C.c_double, dp, dp]
+    lib.moev_bias_corrections.argtypes = [C.c_float, C.c_float, u64, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in ("ckpt_plan_window", "ckpt_plan_n_ops", "ckpt_plan_n_tensors", "ckpt_plan_n_active"):
         getattr(lib, name).argtypes = [vp]
         getattr(lib, name).restype = u32
@@ -242,6 +243,12 @@ def moev_recovery_time(sparse: bool, interval_or_window: float, t_iter_s: float)
 
 
 # ---- plan --------------------------------------------------------------------------------
+def moev_bias_corrections(beta1: float, beta2: float, step: int):
+    b1, b2 = C.c_float(), C.c_float()
+    _check(_lib.moev_bias_corrections(beta1, beta2, step, C.byref(b1), C.byref(b2)))
+    return b1.value, b2.value
+
+
 class Plan:
     """Owner of a moev_plan* (freed with the object)."""
 

@@ -595,6 +595,11 @@ int check_replay_args(moev_plan* p, const moev_adam* adam, const uint8_t* d_acti
   return MOEV_OK;
 }
 
+// bias correction 1 - beta^step: in double, rounded to FP32 once
+float bias_correction(float beta, uint64_t step) {
+  return static_cast<float>(1.0 - std::pow(static_cast<double>(beta), static_cast<double>(step)));
+}
+
 // Argument block of one replay step, everything but the tables of state / gradient pointers and the tile list.
 moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_t* d_active_mask) {
   const auto& h = p->host;
@@ -614,9 +619,8 @@ moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_
   a.eps = adam->eps;
   a.one_minus_beta1 = 1.0f - adam->beta1;
   a.one_minus_beta2 = 1.0f - adam->beta2;
-  // bias corrections 1 - beta^step: in double, rounded to FP32 once
-  a.bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta1), static_cast<double>(adam->step)));
-  a.bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(adam->beta2), static_cast<double>(adam->step)));
+  a.bc1 = bias_correction(adam->beta1, adam->step);
+  a.bc2 = bias_correction(adam->beta2, adam->step);
   a.decay = adam->lr * adam->weight_decay;
   a.has_decay = adam->weight_decay != 0.0f ? 1u : 0u;
   // the plain division / square-root sequences hold for moments in [2^-60, 2^40) if the other operands are ordinary too
@@ -799,6 +803,13 @@ int moev_recovery_time(int sparse, double interval_or_window, double t_iter_s, d
   const double span = interval_or_window * t_iter_s;
   *expected_s = sparse ? span + 0.5 * span : 0.5 * span;  // conversion replays W, then on average half a window more
   *worst_s = sparse ? span + span : span;
+  return MOEV_OK;
+}
+
+int moev_bias_corrections(float beta1, float beta2, uint64_t step, float* bc1, float* bc2) {
+  if (!bc1 || !bc2 || step == 0) return fail(MOEV_E_INVAL, "moev_bias_corrections: null pointer or step 0");
+  *bc1 = bias_correction(beta1, step);
+  *bc2 = bias_correction(beta2, step);
   return MOEV_OK;
 }
 

@@ -241,6 +241,8 @@ int build_plan(const moev_plan_cfg& cfg, HostPlan& p, std::string& err) {
   f.add<uint8_t>(p.width[MOEV_KIND_ADAM_M]);
   f.add<uint8_t>(p.width[MOEV_KIND_ADAM_V]);
   f.add<uint8_t>(p.width[MOEV_KIND_COMPUTE]);
+  // the storage formats too: an F16 snapshot must not load into a BF16 plan of the same widths
+  for (uint8_t fmt : p.fmt) f.add<uint8_t>(fmt);
   for (const auto& t : p.tensors) {
     f.add<uint32_t>(t.op);
     f.add<uint64_t>(t.numel);

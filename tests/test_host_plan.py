@@ -6,6 +6,7 @@ import re
 
 import numpy as np
 import pytest
+import torch
 
 from paper_2412_15411_amd import binding as B
 from paper_2412_15411_amd import workloads as W
@@ -235,3 +236,59 @@ def test_gpu_calls_fail_loudly_without_a_gpu():
     with pytest.raises(B.MoevError) as e:
         B.snapshot_pack(plan, 0, 10, state, addr, cap=B.ckpt_plan_max_packed_bytes(plan))
     assert e.value.code == B.E_HIP
+
+
+def test_plan_hash_covers_the_storage_formats(orc):
+    """A snapshot taken under one precision regime must not pass the header check of a plan with the same element
+    widths and other storage formats: the formats are part of the hash, on both sides alike."""
+    wl = W.fine_grained_stack(n_layers=1, n_routed=8, n_shared=2, d_model=24, d_ff=13, per_slot=2)
+    lib_of = {orc.FMT_F32: B.FMT_F32, orc.FMT_F16: B.FMT_F16, orc.FMT_BF16: B.FMT_BF16, orc.FMT_E4M3: B.FMT_E4M3,
+              orc.FMT_E5M2: B.FMT_E5M2}
+    seen = set()
+    for fmts in ((orc.FMT_F16,) * 4, (orc.FMT_BF16,) * 4, (orc.FMT_F16, orc.FMT_F16, orc.FMT_F16, orc.FMT_BF16),
+                 (orc.FMT_F16, orc.FMT_E4M3, orc.FMT_F16, orc.FMT_E4M3), (orc.FMT_F16, orc.FMT_E5M2, orc.FMT_F16, orc.FMT_E5M2),
+                 (orc.FMT_F32, orc.FMT_F32, orc.FMT_F32, orc.FMT_E4M3)):
+        plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
+                           formats=[lib_of[f] for f in fmts])
+        h = B.ckpt_plan_hash(plan)
+        assert h == orc.plan_hash(model_of(wl, formats=fmts))
+        assert h not in seen
+        seen.add(h)
+    # formats left open are filled in by width before hashing
+    by_width = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, widths=(2, 2, 2, 2))
+    assert B.ckpt_plan_hash(by_width) == orc.plan_hash(model_of(wl, formats=(orc.FMT_F16, orc.FMT_F16, orc.FMT_F16, orc.FMT_BF16)))
+    # and a host snapshot of one regime is refused by the other's plan
+    f16 = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=[B.FMT_F16] * 4)
+    bf16 = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=[B.FMT_BF16] * 4)
+    model = model_of(wl, formats=(orc.FMT_F16,) * 4)
+    st = W.make_low_precision_state(wl, (torch.float16,) * 4, (1.0, 64.0, 65536.0, 1.0), seed=1)
+    snap = orc.pack(model, 1, 77, orc.State(*[[t.view(torch.int16).numpy().view(np.uint16) for t in st[k]]
+                                              for k in ("master", "m", "v", "compute")]))
+    assert B.snapshot_peek(f16, 1, torch.from_numpy(snap))["iter"] == 77
+    with pytest.raises(B.MoevError) as e:
+        B.snapshot_peek(bf16, 1, torch.from_numpy(snap))
+    assert e.value.code == B.E_MISMATCH
+
+
+def test_bias_corrections_agree_with_the_oracle_up_to_100000_steps(orc):
+    """1 - beta^step in double precision, rounded to FP32 once: the library raises beta to the power with the math
+    library, the oracle multiplies step times.  The two must land on the same FP32 value for every step a run can
+    reach (the GPU parity tests only visit small step numbers).  Every step up to 20,000 (beyond ~17,500 even
+    0.999^step is below half an FP32 unit of 1 and both corrections are exactly 1), then 1,000 steps spread up to
+    100,000 (the oracle's product costs `step` multiplications per call)."""
+    rng = np.random.default_rng(3)
+    far = sorted(set(int(x) for x in rng.integers(20_001, 100_001, size=990)) | set(range(99_991, 100_001)))
+    for beta1, beta2 in ((0.9, 0.95), (0.95, 0.999), (0.999, 0.9)):
+        hp = orc.AdamHP(1e-4, beta1, beta2, 1e-8, 0.0)
+        distinct = set()
+        for step in list(range(1, 20_001)) + far:
+            got = B.moev_bias_corrections(beta1, beta2, step)
+            assert got == orc.bias_corrections(hp, step), (beta1, beta2, step)
+            distinct.add(got)
+        assert len(distinct) > 100 and B.moev_bias_corrections(beta1, beta2, 100_000) == (1.0, 1.0)
+    # the closed form's ends
+    assert B.moev_bias_corrections(0.9, 0.999, 10 ** 9) == (1.0, 1.0)
+    b1, _ = B.moev_bias_corrections(0.9, 0.999, 1)
+    assert b1 == float(np.float32(1.0 - float(np.float32(0.9))))
+    with pytest.raises(B.MoevError):
+        B.moev_bias_corrections(0.9, 0.999, 0)

@@ -281,6 +281,52 @@ def test_pack_bytes_by_definition(orc):
         assert not packed[~covered].any()  # padding is zero
 
 
+def _fnv1a64_reference(data: bytes) -> int:
+    h = 0xCBF29CE484222325
+    for byte in data:
+        h = ((h ^ byte) * 0x100000001B3) & ((1 << 64) - 1)
+    return h
+
+
+def _plan_bytes(model) -> bytes:
+    """The byte string the plan hash is defined over (little endian): u32 n_ops, n_tensors, window, align; u8 widths
+    and u8 storage formats of master, m, v, compute (formats left open are filled in by width: 4 -> FP32, 2 -> FP16,
+    bfloat16 for the compute weights, 1 -> E4M3, otherwise 0); per tensor u32 op, u64 numel; per operator u32 slot;
+    per position u32 order."""
+    import struct
+    widths = tuple(model.widths) if len(model.widths) == 4 else (model.widths[0], model.widths[1], model.widths[1], model.widths[2])
+    by_width = lambda kind, w: {4: 1, 2: 3 if kind == 3 else 2, 1: 4}.get(w, 0)
+    fmts = tuple(model.formats) if model.formats is not None else tuple(by_width(k, w) for k, w in enumerate(widths))
+    out = struct.pack("<4I", model.n_ops, model.n_tensors, model.window, model.align) + bytes(widths) + bytes(fmts)
+    for op, numel in model.tensors:
+        out += struct.pack("<IQ", op, numel)
+    out += struct.pack(f"<{model.n_ops}I", *model.slot_of_op) + struct.pack(f"<{model.n_ops}I", *model.order)
+    return out
+
+
+def test_plan_hash_is_fnv1a_of_the_documented_byte_string(orc):
+    """Pins the hash to something outside the oracle: the published FNV-1a vectors fix the function (a wrong prime,
+    offset basis or xor / multiply order fails them), and the plan hash must be that function over the byte string
+    the snapshot format documents (a dropped, reordered or mis-sized field fails)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "fnv1a64_vectors.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        text, want = [x.strip() for x in line.split("->")]
+        data = b"" if text == "EMPTY" else text.encode()
+        assert orc.fnv1a64(data) == int(want, 16) == _fnv1a64_reference(data)
+        n += 1
+    assert n == 3
+    wl = _ragged_workload(seed=4)
+    for model in (model_of(wl), model_of(wl, align=4096), model_of(wl, widths=(2, 1, 2, 1)), model_of(wl, widths=(8, 8, 8, 8)),
+                  model_of(wl, formats=(orc.FMT_BF16, orc.FMT_BF16, orc.FMT_BF16, orc.FMT_BF16)),
+                  model_of(wl, formats=(orc.FMT_E5M2, orc.FMT_E4M3, orc.FMT_BF16, orc.FMT_E5M2)),
+                  model_of(W.tiny_moe()), model_of(W.fine_grained_stack(n_layers=1, n_routed=8, d_model=8, d_ff=4))):
+        assert orc.plan_hash(model) == _fnv1a64_reference(_plan_bytes(model))
+        assert orc.plan_hash(model) == orc.fnv1a64(_plan_bytes(model))
+
+
 def test_plan_hash_distinguishes(orc):
     wl = _ragged_workload(seed=4)
     base = orc.plan_hash(model_of(wl))
@@ -291,6 +337,14 @@ def test_plan_hash_distinguishes(orc):
     assert orc.plan_hash(model_of(wl, widths=(4, 4, 4, 1))) != base
     assert orc.plan_hash(model_of(wl, widths=(4, 4, 2, 2))) != base
     assert orc.plan_hash(model_of(wl)) == base
+    # same widths, another storage format: a snapshot must not load into the other regime
+    f16 = orc.plan_hash(model_of(wl, formats=(orc.FMT_F16,) * 4))
+    assert orc.plan_hash(model_of(wl, formats=(orc.FMT_BF16,) * 4)) != f16
+    assert orc.plan_hash(model_of(wl, formats=(orc.FMT_F16, orc.FMT_F16, orc.FMT_F16, orc.FMT_BF16))) != f16
+    assert orc.plan_hash(model_of(wl, widths=(2, 2, 2, 2))) == orc.plan_hash(
+        model_of(wl, formats=(orc.FMT_F16, orc.FMT_F16, orc.FMT_F16, orc.FMT_BF16)))   # the defaults by width
+    e4 = orc.plan_hash(model_of(wl, formats=(orc.FMT_F16, orc.FMT_E4M3, orc.FMT_F16, orc.FMT_E4M3)))
+    assert orc.plan_hash(model_of(wl, formats=(orc.FMT_F16, orc.FMT_E5M2, orc.FMT_F16, orc.FMT_E4M3))) != e4
 
 
 @pytest.mark.parametrize("align", [16, 256])
