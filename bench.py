@@ -716,18 +716,31 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).fill_(1)
     dst = torch.empty_like(src)
     torch.cuda.synchronize()
-    best = None
-    for _ in range(4):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        B.moev_copy_probe(dst, src, probe_bytes, 0, 1, stream)
-        e1.record(stream)
-        stream.synchronize()
-        ms = e0.elapsed_time(e1)
-        best = ms if best is None else min(best, ms)
+
+    def best_of(fn, reps=4):
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            stream.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best
+
+    best = best_of(lambda: B.moev_copy_probe(dst, src, probe_bytes, 0, 1, stream))
+    read_ms = best_of(lambda: B.moev_stream_probe(1, dst, src, probe_bytes, 0, 1, stream))
+    write_ms = best_of(lambda: B.moev_stream_probe(2, dst, None, probe_bytes, 0x01010101, 1, stream))
+    read_gbs, write_gbs = probe_bytes / (read_ms / 1e3) / 1e9, probe_bytes / (write_ms / 1e3) / 1e9
     out["copy_probe"] = {"bytes_each_way": probe_bytes, "ms": round(best, 4),
                          "GBs": round(2 * probe_bytes / (best / 1e3) / 1e9, 1),
-                         "frac_hbm_peak": round(2 * probe_bytes / (best / 1e3) / 1e9 / HBM_PEAK_GBS, 4)}
+                         "frac_hbm_peak": round(2 * probe_bytes / (best / 1e3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "read_only_GBs": round(read_gbs, 1), "write_only_GBs": round(write_gbs, 1)}
+    # The box's own yardstick for mixed traffic is the plain copy (one-directional streams run faster than any mix of
+    # the two directions); `frac` stays relative to the published 8 TB/s.
+    if roofline["bound"] == "hbm":
+        out["roofline"]["achieved_over_copy_probe"] = round(roofline["achieved"] / out["copy_probe"]["GBs"], 4)
     del src, dst
 
     # ---- drain: host link, measured outside the timed steps --------------------------------

@@ -422,6 +422,14 @@ int uplog_stats(moev_uplog *log, uint64_t *entries, uint64_t *bytes_in_use, uint
 int moev_copy_probe(void *d_dst, const void *d_src, size_t nbytes, uint32_t blocks, int nontemporal,
                     void *stream);
 
+/* moev_stream_probe: the one-directional companions of the copy probe, same access shape (one 4 KB tile per
+ * workgroup).  mode 1: read nbytes from d_src and discard them (d_dst: 16 writable device bytes, which receive a
+ * store only if the data happens to contain one particular 128-bit pattern); mode 2: fill d_dst[nbytes] with the
+ * 32-bit `value`, d_src is not used.  nbytes a multiple of 16, pointers 16-byte aligned.  Read-only, write-only and
+ * copy rates bracket what a kernel with a given read : write mix can reach on the box. */
+int moev_stream_probe(int mode, void *d_dst, const void *d_src, size_t nbytes, uint32_t value, int nontemporal,
+                      void *stream);
+
 /* ---- arithmetic self-check -----------------------------------------------------------------
  * moev_arith_selfcheck: runs, on the GPU, the plain division / square-root sequences of
  * MOEV_TUNE_PLAIN_DIVIDE_SQRT beside the compiler's full IEEE expansions and counts the inputs on

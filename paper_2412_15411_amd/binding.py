@@ -32,7 +32,7 @@ EXPORTS = [
     "ckpt_plan_pack_tile_bytes",
     "moev_tune", "moev_tune_get", "ckpt_plan_upload", "ckpt_plan_device_layout", "ckpt_plan_device_status",
     "snapshot_pack", "snapshot_drain", "snapshot_drain_range", "snapshot_peek", "restore_unpack", "convert_replay", "convert_replay_static", "convert_window_step",
-    "moev_copy_probe", "moev_arith_selfcheck", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
+    "moev_copy_probe", "moev_stream_probe", "moev_arith_selfcheck", "uplog_create", "uplog_free", "uplog_reserve", "uplog_append", "uplog_find", "uplog_replay",
     "uplog_gc", "uplog_stats",
 ]
 
@@ -134,6 +134,7 @@ def _load():
     lib.convert_replay_static.argtypes = [vp, C.POINTER(_Adam), vp, vp, vp, vp]
     lib.convert_window_step.argtypes = [vp, u32, vp, vp, C.POINTER(_Adam), vp, C.POINTER(vp), C.POINTER(_State), vp]
     lib.moev_copy_probe.argtypes = [vp, vp, C.c_size_t, u32, C.c_int, vp]
+    lib.moev_stream_probe.argtypes = [C.c_int, vp, vp, C.c_size_t, u32, C.c_int, vp]
     lib.moev_arith_selfcheck.argtypes = [C.c_int, C.c_float, u32, u64, u64, C.POINTER(u64), vp]
     lib.uplog_create.argtypes = [vp, C.c_size_t, u32, C.POINTER(vp)]
     lib.uplog_free.argtypes = [vp]
@@ -416,6 +417,11 @@ def moev_copy_probe(d_dst, d_src, nbytes: int, blocks: int = 0, nontemporal: int
 
 # ---- upstream logging ring -----------------------------------------------------------------
 ACTIVATION, GRADIENT = 0, 1
+
+
+def moev_stream_probe(mode: int, d_dst, d_src, nbytes: int, value: int = 0, nontemporal: int = 1, stream=None):
+    """mode 1: read d_src[nbytes] only; mode 2: fill d_dst[nbytes] with the 32-bit value."""
+    _check(_lib.moev_stream_probe(mode, _addr(d_dst), _addr(d_src), nbytes, value, nontemporal, _stream(stream)))
 
 
 class UpLog:

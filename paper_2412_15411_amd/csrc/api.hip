@@ -1044,6 +1044,16 @@ int moev_copy_probe(void* d_dst, const void* d_src, size_t nbytes, uint32_t bloc
   return MOEV_OK;
 }
 
+int moev_stream_probe(int mode, void* d_dst, const void* d_src, size_t nbytes, uint32_t value, int nontemporal, void* stream) {
+  if (mode != 1 && mode != 2) return fail(MOEV_E_INVAL, "moev_stream_probe: mode must be 1 (read only) or 2 (write only)");
+  if (!d_dst || (mode == 1 && !d_src) || nbytes == 0 || (nbytes & 15u))
+    return fail(MOEV_E_INVAL, "moev_stream_probe: null pointer or size not a multiple of 16");
+  if (!aligned16(d_dst) || (mode == 1 && !aligned16(d_src))) return fail(MOEV_E_INVAL, "moev_stream_probe: pointers must be 16-byte aligned");
+  if ((nbytes + 4095) / 4096 >= (1ull << 31)) return fail(MOEV_E_RANGE, "moev_stream_probe: too large");
+  MOEV_HIP(moev::launch_stream_probe(mode, d_src, d_dst, nbytes, value, nontemporal != 0, static_cast<hipStream_t>(stream)));
+  return MOEV_OK;
+}
+
 int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* state, void* d_packed, size_t cap,
                   void* stream) {
   if (!p || !d_packed) return fail(MOEV_E_INVAL, "snapshot_pack: null argument");

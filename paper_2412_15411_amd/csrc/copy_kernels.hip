@@ -271,11 +271,46 @@ __global__ __launch_bounds__(kThreads) void k_copy_probe(const uint8_t* __restri
   }
 }
 
+// One-directional streams of the same access shape (one 4 KB tile per workgroup): what the memory
+// system gives a kernel that only reads, or only writes.  Together with the copy they bracket what a
+// kernel with a given read : write mix can reach on the box.
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_read_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ sink,
+                                                         uint64_t nbytes) {
+  const uint64_t o = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * kVec;
+  if (o + kVec > nbytes) return;
+  const u32x4 r = ld<NT>(reinterpret_cast<const u32x4*>(src + o));
+  // keeps the load alive: a store that needs two 32-bit coincidences in the data
+  if ((r.x ^ r.z) == 0x9e3779b9u && (r.y ^ r.w) == 0x7f4a7c15u) *reinterpret_cast<u32x4*>(sink) = r;
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_write_probe(uint8_t* __restrict__ dst, uint64_t nbytes, uint32_t value) {
+  const uint64_t o = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * kVec;
+  if (o + kVec > nbytes) return;
+  st<NT>(reinterpret_cast<u32x4*>(dst + o), u32x4{value, value, value, value});
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------
+hipError_t launch_stream_probe(int mode, const void* src, void* dst, uint64_t nbytes, uint32_t value, bool nontemporal,
+                               hipStream_t s) {
+  const uint32_t blocks = static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec));
+  const uint8_t* sp = static_cast<const uint8_t*>(src);
+  uint8_t* dp = static_cast<uint8_t*>(dst);
+  if (mode == 1) {
+    if (nontemporal) hipLaunchKernelGGL(k_read_probe<true>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes);
+    else hipLaunchKernelGGL(k_read_probe<false>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes);
+  } else {
+    if (nontemporal) hipLaunchKernelGGL(k_write_probe<true>, dim3(blocks), dim3(kThreads), 0, s, dp, nbytes, value);
+    else hipLaunchKernelGGL(k_write_probe<false>, dim3(blocks), dim3(kThreads), 0, s, dp, nbytes, value);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_layout_scan(const ScanJob* d_jobs, uint32_t n_jobs, hipStream_t s) {
   if (n_jobs == 0) return hipSuccess;
   hipLaunchKernelGGL(k_layout_scan, dim3(n_jobs), dim3(kThreads), 0, s, d_jobs);

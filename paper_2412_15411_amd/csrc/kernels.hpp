@@ -73,6 +73,10 @@ hipError_t launch_layout_scan(const ScanJob* d_jobs, uint32_t n_jobs, hipStream_
 hipError_t launch_copy_probe(const void* src, void* dst, uint64_t nbytes, uint32_t blocks, uint32_t unroll,
                              bool nontemporal, hipStream_t s);
 
+// mode 1: read nbytes from src (dst: 16 writable bytes that may receive one store); mode 2: fill dst[nbytes] with value
+hipError_t launch_stream_probe(int mode, const void* src, void* dst, uint64_t nbytes, uint32_t value, bool nontemporal,
+                               hipStream_t s);
+
 // one tile per workgroup: grid = number of tiles, tile = threads * 16 bytes (* 4 elements) * unroll
 bool direct_shape_supported(uint32_t threads, uint32_t unroll);
 hipError_t launch_pack_direct(const CopyArgs& a, uint32_t blocks, uint32_t threads, uint32_t unroll, bool nt,

@@ -559,6 +559,33 @@ def test_host_side_argument_checks(dev):
     assert e.value.code == B.E_INVAL and torch.equal(before, st["master"][0])
 
 
+def test_measurement_probes_move_what_they_say(dev):
+    """The copy / read-only / write-only probes (the yardsticks of bench.py): the copy is exact including a ragged
+    last tile, the write probe fills exactly its range, the read probe leaves its sink alone, bad arguments are refused."""
+    n = (1 << 20) + 4096 + 48
+    src = torch.randint(0, 255, (n + 64,), dtype=torch.uint8, device=dev)
+    dst = torch.full((n + 64,), 0xEE, dtype=torch.uint8, device=dev)
+    for blocks in (0, 7):
+        dst.fill_(0xEE)
+        B.moev_copy_probe(dst, src, n, blocks, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src[:n]) and bool((dst[n:] == 0xEE).all())
+    dst.fill_(0xEE)
+    B.moev_stream_probe(2, dst, None, n, 0x04030201, 0)
+    torch.cuda.synchronize()
+    want = torch.tensor([1, 2, 3, 4], dtype=torch.uint8, device=dev).repeat(n // 4)
+    assert torch.equal(dst[:n], want) and bool((dst[n:] == 0xEE).all())
+    dst.fill_(0xEE)
+    B.moev_stream_probe(1, dst, src, n, 0, 1)
+    torch.cuda.synchronize()
+    assert bool((dst == 0xEE).all())
+    for bad in (lambda: B.moev_stream_probe(3, dst, src, n), lambda: B.moev_stream_probe(1, dst, src, n + 1),
+                lambda: B.moev_stream_probe(1, dst, None, n), lambda: B.moev_stream_probe(2, dst[1:], None, n)):
+        with pytest.raises(B.MoevError) as e:
+            bad()
+        assert e.value.code == B.E_INVAL
+
+
 # ---------------------------------------------------------------------------------------
 # Adam replay
 # ---------------------------------------------------------------------------------------
