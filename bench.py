@@ -63,6 +63,9 @@ def parse_args():
     ap.add_argument("--adam-tile", type=int, default=0)
     ap.add_argument("--copy-blocks", type=int, default=0)
     ap.add_argument("--adam-blocks", type=int, default=0)
+    ap.add_argument("--alloc", default="tensor", choices=["flat", "tensor"], help="how the bench allocates the training state and the "
+                    "gradients: flat = one flat buffer per kind / per iteration with the tensors as views (what flat-partition "
+                    "optimizers do), tensor = every tensor its own allocation (the default).  The library sees pointers either way")
     ap.add_argument("--adam-shape", default="", help="one-tile-per-workgroup shape of the replay as THREADSxUNROLL, e.g. 64x2 "
                     "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -275,7 +278,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     wl = W.ep_rank_share()
     t_setup = time.time()
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
-    st = W.make_state(wl, seed=args.seed, device=dev)
+    st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat")
     state = B.State(st["master"], st["m"], st["v"], st["compute"])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
     packed = torch.empty(B.ckpt_plan_max_packed_bytes(plan), dtype=torch.uint8, device=dev)
@@ -329,7 +332,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"configs[3] {wl.name}", "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
+        "config": {"workload": f"configs[3] {wl.name}", "state_allocation": "one flat buffer per kind" if args.alloc == "flat" else "one allocation per tensor", "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
                    "step": "W x (snapshot_pack + restore_unpack) through one reused packed buffer, HBM-resident; no replay",
                    "step_algorithmic_bytes": step_bytes},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4), "kernels": kernels,
@@ -504,7 +507,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
     formats, d_scales = (0, 0, 0, 0), None
     if dtypes is None:
-        st = W.make_state(wl, seed=args.seed, device=dev)
+        st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat")
     else:
         lib_fmt = {torch.float32: B.FMT_F32, torch.float16: B.FMT_F16, torch.bfloat16: B.FMT_BF16,
                    torch.float8_e4m3fn: B.FMT_E4M3, torch.float8_e5m2: B.FMT_E5M2}
@@ -517,9 +520,8 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     # operators skip their weight-gradient computation (Sec. 3.3), so their entries are None.
     grads = {}
     for i in range(wl.window):
-        full = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev)
-        grads[wl.t0 + i + 1] = [g if wl.slot_of_op[wl.tensors[t][0]] <= i else None for t, g in enumerate(full)]
-        del full
+        grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev, flat=args.alloc == "flat",
+                                            only=[wl.slot_of_op[op] <= i for op, _ in wl.tensors])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=formats)
     if args.persistent:
         B.moev_tune(plan, B.TUNE_PERSISTENT, 1)
@@ -627,6 +629,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"configs[{cfg[1]}] {wl.name}", "regime": args.regime, "element_bytes": list(widths),
+                   "state_allocation": "one flat buffer per kind" if args.alloc == "flat" else "one allocation per tensor",
                    "n_ops": wl.n_ops, "n_params": wl.n_params,
                    "window": wl.window, "step": "W x snapshot_pack + W x (restore_unpack + convert_replay), HBM-resident",
                    "step_algorithmic_bytes": step_bytes},

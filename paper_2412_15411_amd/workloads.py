@@ -12,7 +12,7 @@ and one expert-parallel rank's share of a large MoE.
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import Dict, List, Sequence, Tuple
+from typing import Dict, List, Optional, Sequence, Tuple
 
 import torch
 
@@ -200,10 +200,33 @@ def make_state_tensor(wl: Workload, kind: str, t: int, seed: int = 0, device="cp
     return x.to(torch.bfloat16) if kind == "compute" else x
 
 
-def make_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, List[torch.Tensor]]:
+def _flat_views(numels: Sequence[int], dtype: torch.dtype, device) -> List[torch.Tensor]:
+    """Views into ONE allocation, one per tensor, each starting on a 4 KiB boundary: the way flat-partition optimizers
+    (ZeRO-style) keep a kind of state.  Separate allocations per tensor and one flat buffer per kind are the same
+    to the library (it sees pointers); what differs is where the memory lands physically."""
+    width = torch.empty(0, dtype=dtype).element_size()
+    seg = [(n * width + 4095) // 4096 * 4096 for n in numels]
+    flat = torch.empty(max(sum(seg), 1), dtype=torch.uint8, device=device)
+    out, off = [], 0
+    for n, sz in zip(numels, seg):
+        out.append(flat[off: off + n * width].view(dtype))
+        off += sz
+    return out
+
+
+def make_state(wl: Workload, seed: int = 0, device="cpu", flat: bool = False) -> Dict[str, List[torch.Tensor]]:
     """master ~ N(0, std 0.02), m ~ N(0, std 1e-3), v = N(0, std 1e-3)^2 (so v >= 0),
-    compute = bfloat16 copy of master.  One generator stream per (kind, tensor)."""
+    compute = bfloat16 copy of master.  One generator stream per (kind, tensor).  flat: every kind lives in one
+    flat buffer (same values)."""
     st: Dict[str, List[torch.Tensor]] = {"master": [], "m": [], "v": [], "compute": []}
+    if flat:
+        numels = [n for _, n in wl.tensors]
+        st = {k: _flat_views(numels, torch.bfloat16 if k == "compute" else torch.float32, device) for k in st}
+        for t in range(wl.n_tensors):
+            for k in ("master", "m", "v"):
+                st[k][t].copy_(make_state_tensor(wl, k, t, seed, device))
+            st["compute"][t].copy_(st["master"][t])
+        return st
     for t in range(wl.n_tensors):
         p = make_state_tensor(wl, "master", t, seed, device)
         st["master"].append(p)
@@ -213,17 +236,30 @@ def make_state(wl: Workload, seed: int = 0, device="cpu") -> Dict[str, List[torc
     return st
 
 
-def make_grads(wl: Workload, step: int, seed: int = 0, device="cpu") -> List[torch.Tensor]:
+def make_grads(wl: Workload, step: int, seed: int = 0, device="cpu", flat: bool = False,
+               only: Optional[Sequence[bool]] = None) -> List[Optional[torch.Tensor]]:
     """Gradients of iteration `step`: N(0, std 1e-3), fresh per (step, tensor).  With
-    wl.heavy_tail an independent uniform draw marks 5% of the entries, which are scaled by 100."""
-    out = []
+    wl.heavy_tail an independent uniform draw marks 5% of the entries, which are scaled by 100.
+    only[t] False: no gradient for tensor t (None in the result); flat: the gradients share one flat buffer."""
+    want = [True] * wl.n_tensors if only is None else list(only)
+    views = None
+    if flat:
+        views = iter(_flat_views([n for (_, n), w in zip(wl.tensors, want) if w], torch.float32, device))
+    out: List[Optional[torch.Tensor]] = []
     for t, (_, n) in enumerate(wl.tensors):
+        if not want[t]:
+            out.append(None)
+            continue
         g = torch.empty(n, dtype=torch.float32, device=device)
         g.normal_(0.0, 1e-3, generator=_gen(device, stream_seed(seed, _STREAM["grad"], t, step)))
         if wl.heavy_tail:
             u = torch.empty(n, dtype=torch.float32, device=device)
             u.uniform_(0.0, 1.0, generator=_gen(device, stream_seed(seed, _STREAM["tail"], t, step)))
             g = torch.where(u < 0.05, g * 100.0, g)
+        if views is not None:
+            dst = next(views)
+            dst.copy_(g)
+            g = dst
         out.append(g)
     return out
 
