@@ -70,6 +70,8 @@ def parse_args():
                     "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-regions", type=int, default=-1)
+    ap.add_argument("--paired-tiles", type=int, default=-1, help="0: the replay takes 1 KB of consecutive bytes per stream and wavefront "
+                    "instead of two 512-byte pieces 32 KiB apart")
     ap.add_argument("--plain-divide-sqrt", type=int, default=-1, help="0: always the full IEEE division / square-root sequences in the replay")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
@@ -540,6 +542,8 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
     if args.plain_divide_sqrt >= 0:
         B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, args.plain_divide_sqrt)
+    if args.paired_tiles >= 0:
+        B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles)
     packed = [torch.empty(B.ckpt_plan_packed_bytes(plan, k), dtype=torch.uint8, device=dev) for k in range(wl.window)]
     mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()

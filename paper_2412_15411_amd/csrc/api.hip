@@ -117,6 +117,7 @@ struct moev_plan {
   int64_t nontemporal = 1;
   int64_t xcd_regions = 1;           // one tile per workgroup: contiguous eighth of the tiles per XCD
   int64_t plain_divide_sqrt = 1;     // low-precision replay: plain division / square root sequences where in range
+  int64_t paired_tiles = 1;          // FP32 replay, 64 x 1 shape: two 512-byte pieces 32 KiB apart per stream and wavefront
 
   // Accesses per lane of the pack of one slot.  Measured: one 16-byte access per lane is best when the slot's
   // segments are large (117-235 MB: 6.55 vs 6.25 TB/s) or all FP32 state; slots that gather many small
@@ -519,6 +520,22 @@ bool fp32_regime(const moev::HostPlan& h) {
   return h.fmt[MOEV_KIND_MASTER] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_ADAM_M] == MOEV_FMT_F32 &&
          h.fmt[MOEV_KIND_ADAM_V] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_COMPUTE] == MOEV_FMT_BF16;
 }
+// paired tiles apply to the default one-tile-per-workgroup shape of the FP32 regime only
+bool replay_paired(const moev_plan* p) {
+  return p->paired_tiles && !p->persistent && p->adam_threads == 64 && p->adam_unroll == 1 && fp32_regime(p->host);
+}
+
+// tiles of one tensor under the paired shape; `master` locates the tensor inside its 64 KiB address block
+uint64_t paired_tiles_of(uint64_t numel, const void* master) {
+  if (numel == 0) return 0;
+  const uint64_t shift = (reinterpret_cast<uintptr_t>(master) & 0xffffu) >> 2;
+  return (numel + shift + moev::kPairedBlockElems - 1) / moev::kPairedBlockElems * moev::kPairedTilesPerBlock;
+}
+// ... when the pointer is not known to the host: the largest shift a 16-byte aligned pointer can have
+uint64_t paired_tiles_bound(uint64_t numel) {
+  return numel ? (numel + (moev::kPairedBlockElems - 4) + moev::kPairedBlockElems - 1) / moev::kPairedBlockElems * moev::kPairedTilesPerBlock : 0;
+}
+
 // restore_unpack re-derives the compute weights of newly active operators in this case only; in the
 // other regimes the replay step that follows the load writes them
 bool derives_compute(const moev::HostPlan& h) {
@@ -612,6 +629,7 @@ moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_
   a.xcd_regions = static_cast<uint32_t>(p->xcd_regions);
   a.n_tensors = h.n_tensors;
   a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
+  a.paired = replay_paired(p) ? 1u : 0u;
   a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
   a.lr = adam->lr;
   a.beta1 = adam->beta1;
@@ -689,7 +707,8 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles
   uint64_t bound = 0;
   for (uint32_t t = 0; t < h.n_tensors; ++t)
-    if (grads[t]) bound += tiles_of(h.tensors[t].numel, a.tile_elems);
+    if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t]) : tiles_of(h.tensors[t].numel, a.tile_elems);
+  if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "replay: too many tiles for one launch");
   return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound), fused_slot, d_packed, s);
 }
 
@@ -900,6 +919,9 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
     case MOEV_TUNE_PLAIN_DIVIDE_SQRT:
       p->plain_divide_sqrt = value ? 1 : 0;
       break;
+    case MOEV_TUNE_PAIRED_TILES:
+      p->paired_tiles = value ? 1 : 0;
+      break;
     case MOEV_TUNE_COPY_THREADS:
       if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->copy_unroll)))
         return fail(MOEV_E_INVAL, "unsupported (threads, unroll) launch shape");
@@ -951,6 +973,7 @@ int64_t moev_tune_get(const moev_plan* p, int knob) {
     case MOEV_TUNE_PERSISTENT: return p->persistent;
     case MOEV_TUNE_XCD_REGIONS: return p->xcd_regions;
     case MOEV_TUNE_PLAIN_DIVIDE_SQRT: return p->plain_divide_sqrt;
+    case MOEV_TUNE_PAIRED_TILES: return p->paired_tiles;
     case MOEV_TUNE_COPY_THREADS: return p->copy_threads;
     case MOEV_TUNE_COPY_UNROLL: return p->copy_unroll_auto ? 0 : p->copy_unroll;
     case MOEV_TUNE_UNPACK_THREADS: return p->unpack_threads;
@@ -1192,7 +1215,13 @@ int convert_replay_static(moev_plan* p, const moev_adam* adam, const uint8_t* d_
   a.grads = d_grad_table;
   // the gradient table lives on the device, so the host cannot tell which entries are null: the grid covers
   // the tiles of every tensor, and workgroups beyond the step's compacted list exit at once
-  return launch_replay_direct(p, a, adam, d_scratch, direct_grid(p->tensor_tiles), -1, nullptr, s);
+  uint64_t bound = p->tensor_tiles;
+  if (a.paired) {
+    bound = 0;
+    for (const auto& t : h.tensors) bound += paired_tiles_bound(t.numel);
+    if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "convert_replay_static: too many tiles for one launch");
+  }
+  return launch_replay_direct(p, a, adam, d_scratch, direct_grid(bound), -1, nullptr, s);
 }
 
 int convert_window_step(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_adam* adam,

@@ -77,7 +77,7 @@ class DeviceState:
 
 
 def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=None, nt=None,
-              copy_shape=None, adam_shape=None, xcd_regions=None):
+              copy_shape=None, adam_shape=None, xcd_regions=None, paired=None):
     """tile / blocks / adam_tile / adam_blocks select the fixed-grid launch shape with those values;
     copy_shape / adam_shape = (threads, unroll) select a one-tile-per-workgroup shape (the default)."""
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order,
@@ -99,6 +99,8 @@ def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=N
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, nt)
     if xcd_regions is not None:
         B.moev_tune(plan, B.TUNE_XCD_REGIONS, xcd_regions)
+    if paired is not None:
+        B.moev_tune(plan, B.TUNE_PAIRED_TILES, paired)
     return plan
 
 
@@ -607,6 +609,7 @@ def _compare_adam(ds, ref, label=""):
     return worst
 
 
+@pytest.mark.parametrize("paired", [1, 0], ids=["paired_tiles", "consecutive_tiles"])
 @pytest.mark.parametrize("plain", [1, 0], ids=["plain_divide_sqrt", "full_divide_sqrt"])
 @pytest.mark.parametrize("seed,wd,heavy,adam_tile,blocks,nt,shape", [
     (1, 0.0, False, None, None, 1, None), (2, 0.1, True, None, None, 0, (64, 1)), (3, 0.0, True, None, None, 1, (512, 2)),
@@ -614,7 +617,7 @@ def _compare_adam(ds, ref, label=""):
     (1, 0.0, False, 8192, None, 1, None), (2, 0.1, True, 1024, 3, 1, None), (3, 0.0, True, 4096, 1, 0, None),
     (4, 0.01, False, 16384, 9, 0, None),
 ])
-def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt, shape, plain):
+def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks, nt, shape, plain, paired):
     """One replayed iteration on ragged tensors with a mixed active/frozen mask: FP32 state within
     1e-6 relative of the oracle (expected bit-identical), frozen tensors and guards untouched.  Both
     with the plain division / square-root sequences where the operands allow them (the default) and
@@ -625,7 +628,9 @@ def test_adam_replay_matches_oracle(orc, dev, seed, wd, heavy, adam_tile, blocks
     st_cpu = W.make_state(wl, seed=seed)
     ds = DeviceState(st_cpu, dev)
     ref = state_of(st_cpu)
-    plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt, adam_shape=shape)
+    if not paired and (shape not in (None, (64, 1)) or adam_tile):
+        pytest.skip("the paired tiles exist for the 64 x 1 one-tile-per-workgroup shape only: nothing to switch off")
+    plan = make_plan(wl, adam_tile=adam_tile, adam_blocks=blocks, nt=nt, adam_shape=shape, paired=paired)
     B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, plain)
     rng = np.random.default_rng(seed)
     mask_np = (rng.random(wl.n_ops) < 0.6).astype(np.uint8)
@@ -796,6 +801,65 @@ def test_window_without_xcd_regions(orc, dev, fused):
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "ragged-window-no-regions")
     assert rebuilt.guards_intact()
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
+def test_window_with_consecutive_tiles(orc, dev, fused):
+    """The replay's paired tiles switched off (every wavefront takes 1 KB of consecutive bytes per stream)."""
+    wl = ragged_workload(80, n_ops=10, window=4, with_empty=True)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=8, align=256, fused=fused, paired=0)
+    assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
+    _compare_adam(rebuilt, dense, "ragged-window-consecutive")
+    assert rebuilt.guards_intact()
+
+
+def test_paired_tiles_cover_every_element_for_any_pointer_alignment(orc, dev):
+    """The paired tile grid follows the address of the master weights: tensors of block-multiple and ragged lengths at
+    every kind of offset inside a 64 KiB block (0, 16 bytes, just below 32 KiB, just above, just below 64 KiB), with the
+    other streams at other offsets: every element is updated exactly once, nothing outside is touched."""
+    lengths = [16384 * 3, 16384 * 2 + 8192, 16384 + 1, 8191, 257, 3, 40000, 1]
+    offsets = [0, 16, 32768 - 16, 32768 + 512, 65536 - 16, 4096, 16384, 49152 + 48]
+    wl = W.Workload("aligned", [(e, n) for e, n in enumerate(lengths)], [0] * len(lengths), 1)
+    model, hp = model_of(wl), hp_of(wl)
+    st_cpu = W.make_state(wl, seed=31)
+    grads_cpu = W.make_grads(wl, 11, seed=31)
+    ref = state_of(st_cpu)
+    orc.replay_step(model, hp, 11, np.ones(wl.n_ops, dtype=np.uint8), [np_of(g) for g in grads_cpu], ref)
+    guard = 256
+    views, arenas = {k: [] for k in KINDS}, []
+    for t, n in enumerate(lengths):
+        for q, kind in enumerate(KINDS + ("grad",)):
+            width = 2 if kind == "compute" else 4
+            off = offsets[(t + 3 * q) % len(offsets)] if kind != "master" else offsets[t]
+            arena = torch.full((65536 * 2 + off + n * width + guard,), 0x5A, dtype=torch.uint8, device=dev)
+            base = (-arena.data_ptr()) % 65536 + off           # the tensor starts `off` bytes into a 64 KiB block
+            src = grads_cpu[t] if kind == "grad" else st_cpu[kind][t]
+            view = arena[base: base + n * width].view(src.dtype)
+            view.copy_(src)
+            assert view.data_ptr() % 65536 == off
+            arenas.append((arena, base, n * width))
+            if kind == "grad":
+                views.setdefault("grad", []).append(view)
+            else:
+                views[kind].append(view)
+    plan = make_plan(wl)
+    assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == 1
+    mask = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
+    B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, 11, mask, views["grad"],
+                     B.State(*[views[k] for k in KINDS]))
+    torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan)
+    import oracle
+    got = oracle.State(*[[np_of(v) for v in views[k]] for k in KINDS])
+    for k in ("master", "m", "v"):
+        for t, (x, y) in enumerate(zip(got.kinds()[k], ref.kinds()[k])):
+            assert max_rel_err(x, y) <= REL_TOL, f"{k}[{t}] (length {lengths[t]}, offset {offsets[t]})"
+    for t, (c, p, cr, pr) in enumerate(zip(got.compute, got.master, ref.compute, ref.master)):
+        same = p.view(np.uint32) == pr.view(np.uint32)
+        assert np.array_equal(c[same], cr[same]), f"compute[{t}]"
+    for arena, base, nbytes in arenas:
+        a = arena.cpu().numpy()
+        assert (a[:base] == 0x5A).all() and (a[base + nbytes:] == 0x5A).all()
 
 
 def test_window_ragged_small_grid(orc, dev):
