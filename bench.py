@@ -70,8 +70,12 @@ def parse_args():
                     "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--xcd-regions", type=int, default=-1)
-    ap.add_argument("--paired-tiles", type=int, default=-1, help="0: the replay takes 1 KB of consecutive bytes per stream and wavefront "
-                    "instead of two 512-byte pieces 32 KiB apart")
+    ap.add_argument("--paired-tiles", type=int, default=-1, help="replay: distance in bytes between the two 512-byte pieces a wavefront "
+                    "takes per stream (default 32768; a power of two in [512, 4 MiB]); 0: 1 KB of consecutive bytes")
+    ap.add_argument("--paired-tiles-sweep", action="store_true", help="after the timed steps: the replay of the last window iteration "
+                    "timed at every piece distance from 512 B to 4 MiB in this process (same tensors, same placement)")
+    ap.add_argument("--pair-distance-sweep", action="store_true", help="copy probe with two 512-byte pieces per wavefront instruction, "
+                    "swept over their distance (512 B .. 2 MiB): shows the address bit the paired tiles exploit")
     ap.add_argument("--plain-divide-sqrt", type=int, default=-1, help="0: always the full IEEE division / square-root sequences in the replay")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
@@ -271,6 +275,29 @@ def cpu_baseline(cfg_name, seed, regime="fp32"):
 
 
 # ---------------------------------------------------------------------------------------
+def apply_launch_knobs(args, plan, B):
+    """The launch-shape flags of the command line, set on a fresh plan."""
+    if args.persistent:
+        B.moev_tune(plan, B.TUNE_PERSISTENT, 1)
+    for knob, val in ((B.TUNE_COPY_TILE_BYTES, args.copy_tile), (B.TUNE_ADAM_TILE_ELEMS, args.adam_tile),
+                      (B.TUNE_COPY_MAX_BLOCKS, args.copy_blocks), (B.TUNE_ADAM_MAX_BLOCKS, args.adam_blocks)):
+        if val:
+            B.moev_tune(plan, knob, val)
+    if args.adam_shape:
+        threads, unroll = (int(x) for x in args.adam_shape.split("x"))
+        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, 1)
+        B.moev_tune(plan, B.TUNE_ADAM_THREADS, threads)
+        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, unroll)
+    if args.nontemporal >= 0:
+        B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
+    if args.xcd_regions >= 0:
+        B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
+    if args.plain_divide_sqrt >= 0:
+        B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, args.plain_divide_sqrt)
+    if args.paired_tiles >= 0:
+        B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles)
+
+
 def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     """configs[3]: one GPU's share of a large MoE (180 GB of state resident in HBM).  The packed
     snapshots of a window (245 GB) cannot be resident next to the state, so a step here is
@@ -283,6 +310,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat")
     state = B.State(st["master"], st["m"], st["v"], st["compute"])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+    apply_launch_knobs(args, plan, B)
     packed = torch.empty(B.ckpt_plan_max_packed_bytes(plan), dtype=torch.uint8, device=dev)
     mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
@@ -525,25 +553,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev, flat=args.alloc == "flat",
                                             only=[wl.slot_of_op[op] <= i for op, _ in wl.tensors])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=formats)
-    if args.persistent:
-        B.moev_tune(plan, B.TUNE_PERSISTENT, 1)
-    for knob, val in ((B.TUNE_COPY_TILE_BYTES, args.copy_tile), (B.TUNE_ADAM_TILE_ELEMS, args.adam_tile),
-                      (B.TUNE_COPY_MAX_BLOCKS, args.copy_blocks), (B.TUNE_ADAM_MAX_BLOCKS, args.adam_blocks)):
-        if val:
-            B.moev_tune(plan, knob, val)
-    if args.adam_shape:
-        threads, unroll = (int(x) for x in args.adam_shape.split("x"))
-        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, 1)
-        B.moev_tune(plan, B.TUNE_ADAM_THREADS, threads)
-        B.moev_tune(plan, B.TUNE_ADAM_UNROLL, unroll)
-    if args.nontemporal >= 0:
-        B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
-    if args.xcd_regions >= 0:
-        B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
-    if args.plain_divide_sqrt >= 0:
-        B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, args.plain_divide_sqrt)
-    if args.paired_tiles >= 0:
-        B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles)
+    apply_launch_knobs(args, plan, B)
     packed = [torch.empty(B.ckpt_plan_packed_bytes(plan, k), dtype=torch.uint8, device=dev) for k in range(wl.window)]
     mask = torch.zeros(wl.n_ops, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()
@@ -677,6 +687,28 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     if dtypes is None:   # the fused kernel exists for the FP32 regime; elsewhere the call runs the two kernels unfused
         out["fused_conversion"] = measure_fused()
 
+    # ---- the replay at every piece distance of the paired tiles, same process and tensors ---------------------
+    if args.paired_tiles_sweep and dtypes is None and not args.persistent:
+        last = wl.window - 1   # every operator active (the mask is in that state after a window)
+        sweep = {}
+        for dist in [0] + [1 << b for b in range(9, 23)]:
+            B.moev_tune(plan, B.TUNE_PAIRED_TILES, dist)
+            run = lambda: B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + wl.window, mask,
+                                           grads[wl.t0 + wl.window], state, stream=stream)
+            for _ in range(2):
+                run()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(8):
+                run()
+            e1.record(stream)
+            stream.synchronize()
+            sweep[str(dist)] = round(8 * replay_bytes(wl, last, widths) / (e0.elapsed_time(e1) / 1e3) / 1e9, 1)
+        B.ckpt_plan_device_status(plan, stream)
+        B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles if args.paired_tiles >= 0 else 1)
+        out["paired_tiles_sweep"] = {"what": "replay GB/s, all operators active, by distance in bytes between the two 512-byte pieces "
+                                     "a wavefront takes per stream (0 and 512: consecutive bytes)", "GBs": sweep}
+
     # ---- launch-bound windows: the same step replayed from a HIP graph -------------------------------------
     # (with resident tables every call enqueues kernels only; all gradient pointers are passed in every
     # iteration so that the pointer table stays the same)
@@ -748,6 +780,17 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     # the two directions); `frac` stays relative to the published 8 TB/s.
     if roofline["bound"] == "hbm":
         out["roofline"]["achieved_over_copy_probe"] = round(roofline["achieved"] / out["copy_probe"]["GBs"], 4)
+    if args.pair_distance_sweep:
+        # the same copy with every wavefront instruction covering two 512-byte pieces D bytes apart (D = 512: consecutive)
+        sweep = {}
+        for log2 in range(9, 23):
+            dist = 1 << log2
+            if src.data_ptr() % (2 * dist) or dst.data_ptr() % (2 * dist):
+                break
+            ms = best_of(lambda: B.moev_stream_probe(3, dst, src, probe_bytes, dist, 1, stream))
+            sweep[str(dist)] = round(2 * probe_bytes / (ms / 1e3) / 1e9, 1)
+        assert torch.equal(dst[-(1 << 20):], src[-(1 << 20):])
+        out["copy_probe"]["piece_distance_sweep_GBs"] = sweep
     del src, dst
 
     # ---- drain: host link, measured outside the timed steps --------------------------------

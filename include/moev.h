@@ -196,11 +196,13 @@ enum {
                                     compiler's IEEE sequences WITHOUT their rescaling and special-case steps, which do
                                     nothing for such operands: same results, ~20% fewer instructions; 0 = always the
                                     full sequences */
-  MOEV_TUNE_PAIRED_TILES = 14      /* replay, FP32 regime, 64 x 1 shape (the default): 1 (default) = every wavefront takes, per
-                                    stream, two 512-byte pieces whose addresses differ in bit 15 only (32 KiB apart) instead
-                                    of 1 KB of consecutive bytes; on MI355X the memory system serves such pairs faster.  The
+  MOEV_TUNE_PAIRED_TILES = 14      /* replay, FP32 regime, 64 x 1 shape (the default): every wavefront takes, per stream, two
+                                    512-byte pieces this many bytes apart instead of 1 KB of consecutive bytes.  32768 (default;
+                                    1 selects it too): the addresses of a pair differ in bit 15 only, and on MI355X the memory
+                                    system serves such pairs faster.  0 = consecutive tiles; any power of two in [512, 4 MiB] is
+                                    accepted so that the distance can be swept (512 is the consecutive layout again).  The
                                     pairing follows the address of each tensor's master weights; other streams profit when
-                                    their pointers are congruent to it modulo 64 KiB.  Same results either way. */
+                                    their pointers are congruent to it modulo twice the distance.  Same results either way. */
 };
 
 const char *moev_last_error(void);
@@ -431,7 +433,11 @@ int moev_copy_probe(void *d_dst, const void *d_src, size_t nbytes, uint32_t bloc
  * workgroup).  mode 1: read nbytes from d_src and discard them (d_dst: 16 writable device bytes, which receive a
  * store only if the data happens to contain one particular 128-bit pattern); mode 2: fill d_dst[nbytes] with the
  * 32-bit `value`, d_src is not used.  nbytes a multiple of 16, pointers 16-byte aligned.  Read-only, write-only and
- * copy rates bracket what a kernel with a given read : write mix can reach on the box. */
+ * copy rates bracket what a kernel with a given read : write mix can reach on the box.
+ * mode 3: copy d_src to d_dst with every wavefront instruction covering two 512-byte pieces `value` bytes apart
+ * (a power of two in [512, 2^30]; 512 = 1 KB of consecutive bytes, 32768 = the geometry of the replay's paired tiles,
+ * MOEV_TUNE_PAIRED_TILES); nbytes and both pointers must be multiples of 2 x value (MOEV_E_INVAL otherwise).  Sweeping
+ * the distance shows which address bit the memory system rewards. */
 int moev_stream_probe(int mode, void *d_dst, const void *d_src, size_t nbytes, uint32_t value, int nontemporal,
                       void *stream);
 

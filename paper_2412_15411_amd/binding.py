@@ -420,7 +420,8 @@ ACTIVATION, GRADIENT = 0, 1
 
 
 def moev_stream_probe(mode: int, d_dst, d_src, nbytes: int, value: int = 0, nontemporal: int = 1, stream=None):
-    """mode 1: read d_src[nbytes] only; mode 2: fill d_dst[nbytes] with the 32-bit value."""
+    """mode 1: read d_src[nbytes] only; mode 2: fill d_dst[nbytes] with the 32-bit value; mode 3: copy with two 512-byte
+    pieces `value` bytes apart per wavefront instruction (size and pointers multiples of 2 x value)."""
     _check(_lib.moev_stream_probe(mode, _addr(d_dst), _addr(d_src), nbytes, value, nontemporal, _stream(stream)))
 
 

@@ -19,22 +19,21 @@ namespace {
 // ------------------------------------------------------------------------------------
 // Paired tiles.  On this part two 512-byte pieces of a stream whose addresses differ only in bit 15
 // (32 KiB apart, the lower one with that bit clear) are served markedly faster when they are requested
-// together than when each is requested with its neighbours (replay: +7 % over consecutive 1 KB tiles;
-// pairs that straddle, i.e. the lower piece has the bit set, are slower than consecutive tiles).  A
-// paired tile is one wavefront's work: lanes 0-31 take 128 consecutive FP32 elements, lanes 32-63 the
-// 128 elements 8192 further; 64 such tiles cover a block of 16384 elements (64 KiB).  The block grid is
-// laid over the ADDRESSES of the master weights: element e of a tensor whose master pointer sits `shift`
-// elements into a 64 KiB block has grid position e + shift, so that the pairing is right for the master
-// stream and for every other stream whose pointer is congruent to it modulo 64 KiB (separately allocated
+// together than when each is requested with its neighbours (replay: +4-7 % over consecutive 1 KB tiles;
+// pairs that straddle, i.e. the lower piece has the bit set, are slower than consecutive tiles, and so
+// are most other distances).  A paired tile is one wavefront's work: lanes 0-31 take 128 consecutive FP32
+// elements, lanes 32-63 the 128 elements 2^L further (L = 13: 32 KiB, the default; the distance is a launch
+// parameter so that it can be swept); 2^(L-7) such tiles cover a block of 2^(L+1) elements.  The block grid
+// is laid over the ADDRESSES of the master weights: element e of a tensor whose master pointer sits `shift`
+// elements into a block has grid position e + shift, so that the pairing is right for the master stream and
+// for every other stream whose pointer is congruent to it modulo the block size (separately allocated
 // tensors usually are); positions below `shift` and beyond the tensor's end are idle lanes.
 // ------------------------------------------------------------------------------------
-constexpr uint32_t kPairBlock = 16384, kPairHalf = 8192, kPairPiece = 128, kPairTilesPerBlock = kPairBlock / (2 * kPairPiece);
-
-__device__ __forceinline__ uint32_t pair_shift(const void* master) {
-  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(master) & 0xffffu) >> 2;
+__device__ __forceinline__ uint32_t pair_shift(const void* master, uint32_t L) {
+  return (static_cast<uint32_t>(reinterpret_cast<uintptr_t>(master)) & ((8u << L) - 1u)) >> 2;
 }
-__device__ __forceinline__ uint64_t paired_tiles(uint64_t numel, uint32_t shift) {
-  return numel ? (numel + shift + kPairBlock - 1) / kPairBlock * kPairTilesPerBlock : 0;
+__device__ __forceinline__ uint64_t paired_tiles(uint64_t numel, uint32_t shift, uint32_t L) {
+  return numel ? ((numel + shift + (2u << L) - 1) >> (L + 1)) << (L - 7) : 0;
 }
 
 // Tile list of one replay step: a tensor contributes its tiles only if its operator is active
@@ -51,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void k_active_scan(const AdamArgs a, uint
       const bool active = a.mask[a.op_of_tensor[t]] != 0;
       const bool has_grad = a.grads[t] != nullptr;
       if (active && !has_grad && numel) *a.status = 2u;  // reported by the status query, tensor skipped
-      if (active && has_grad) tiles = a.paired ? paired_tiles(numel, pair_shift(a.ptrs[t])) : (numel + a.tile_elems - 1) / a.tile_elems;
+      if (active && has_grad) tiles = a.paired ? paired_tiles(numel, pair_shift(a.ptrs[t], a.paired), a.paired) : (numel + a.tile_elems - 1) / a.tile_elems;
     }
     uint64_t all;
     const uint64_t excl = block_exclusive_scan(tiles, lds, &all);
@@ -227,10 +226,11 @@ __device__ __forceinline__ void adam_range(const float* Ps, const float* Ms, con
 template <bool NT>
 __device__ __forceinline__ void adam_tile_paired(const float* Ps, const float* Ms, const float* Vs,
                                                  const float* __restrict__ G, float* P, float* M, float* V,
-                                                 uint16_t* __restrict__ C, uint64_t numel, uint32_t shift, uint32_t tile,
+                                                 uint16_t* __restrict__ C, uint64_t numel, uint32_t L, uint32_t tile,
                                                  const AdamConst& c, bool plain) {
-  const uint64_t grid_pos = static_cast<uint64_t>(tile / kPairTilesPerBlock) * kPairBlock + (threadIdx.x >> 5) * kPairHalf +
-                            (tile % kPairTilesPerBlock) * kPairPiece + 4u * (threadIdx.x & 31u);
+  const uint32_t shift = pair_shift(P, L);
+  const uint64_t grid_pos = (static_cast<uint64_t>(tile >> (L - 7)) << (L + 1)) + (static_cast<uint64_t>(threadIdx.x >> 5) << L) +
+                            ((tile & ((1u << (L - 7)) - 1u)) << 7) + 4u * (threadIdx.x & 31u);
   if (grid_pos < shift) return;  // in front of the tensor's first element (shift and grid_pos are multiples of four)
   const uint64_t i = grid_pos - shift;
   if (i + 4 <= numel) {
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(T) void k_adam_direct(MOEV_ADAM_TABLES, const AdamA
   uint16_t* C = static_cast<uint16_t*>(ptrs[3ull * a.n_tensors + t]);
   if constexpr (T == 64 && U == 1) {
     if (a.paired) {
-      adam_tile_paired<NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, numel, pair_shift(P), tile - tile_start[t],
+      adam_tile_paired<NT>(P, M, V, static_cast<const float*>(grads[t]), P, M, V, C, numel, a.paired, tile - tile_start[t],
                            adam_const(a), a.plain_divide_sqrt != 0);
       return;
     }
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(T) void k_adam_fused(MOEV_ADAM_TABLES, const uint64
   }
   if constexpr (T == 64 && U == 1) {
     if (a.paired) {
-      adam_tile_paired<NT>(Ps, Ms, Vs, static_cast<const float*>(grads[t]), P, M, V, C, numel, pair_shift(P), tile - tile_start[t],
+      adam_tile_paired<NT>(Ps, Ms, Vs, static_cast<const float*>(grads[t]), P, M, V, C, numel, a.paired, tile - tile_start[t],
                            adam_const(a), a.plain_divide_sqrt != 0);
       return;
     }

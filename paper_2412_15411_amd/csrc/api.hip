@@ -117,7 +117,8 @@ struct moev_plan {
   int64_t nontemporal = 1;
   int64_t xcd_regions = 1;           // one tile per workgroup: contiguous eighth of the tiles per XCD
   int64_t plain_divide_sqrt = 1;     // low-precision replay: plain division / square root sequences where in range
-  int64_t paired_tiles = 1;          // FP32 replay, 64 x 1 shape: two 512-byte pieces 32 KiB apart per stream and wavefront
+  int64_t paired_tiles = 32768;      // FP32 replay, 64 x 1 shape: two 512-byte pieces this many bytes apart per stream and
+                                     // wavefront (a power of two); 0: consecutive tiles
 
   // Accesses per lane of the pack of one slot.  Measured: one 16-byte access per lane is best when the slot's
   // segments are large (117-235 MB: 6.55 vs 6.25 TB/s) or all FP32 state; slots that gather many small
@@ -525,15 +526,19 @@ bool replay_paired(const moev_plan* p) {
   return p->paired_tiles && !p->persistent && p->adam_threads == 64 && p->adam_unroll == 1 && fp32_regime(p->host);
 }
 
-// tiles of one tensor under the paired shape; `master` locates the tensor inside its 64 KiB address block
-uint64_t paired_tiles_of(uint64_t numel, const void* master) {
+// log2 of the piece distance in FP32 elements (the kernels' parameter), 0 when the replay is not paired
+uint32_t pair_log2(const moev_plan* p) {
+  return replay_paired(p) ? static_cast<uint32_t>(__builtin_ctzll(static_cast<uint64_t>(p->paired_tiles))) - 2u : 0u;
+}
+// tiles of one tensor under the paired shape; `master` locates the tensor inside its address block of 2^(L+1) elements
+uint64_t paired_tiles_of(uint64_t numel, const void* master, uint32_t L) {
   if (numel == 0) return 0;
-  const uint64_t shift = (reinterpret_cast<uintptr_t>(master) & 0xffffu) >> 2;
-  return (numel + shift + moev::kPairedBlockElems - 1) / moev::kPairedBlockElems * moev::kPairedTilesPerBlock;
+  const uint64_t shift = (reinterpret_cast<uintptr_t>(master) & ((8ull << L) - 1)) >> 2;
+  return ((numel + shift + (2ull << L) - 1) >> (L + 1)) << (L - 7);
 }
 // ... when the pointer is not known to the host: the largest shift a 16-byte aligned pointer can have
-uint64_t paired_tiles_bound(uint64_t numel) {
-  return numel ? (numel + (moev::kPairedBlockElems - 4) + moev::kPairedBlockElems - 1) / moev::kPairedBlockElems * moev::kPairedTilesPerBlock : 0;
+uint64_t paired_tiles_bound(uint64_t numel, uint32_t L) {
+  return numel ? ((numel + ((2ull << L) - 4) + (2ull << L) - 1) >> (L + 1)) << (L - 7) : 0;
 }
 
 // restore_unpack re-derives the compute weights of newly active operators in this case only; in the
@@ -629,7 +634,7 @@ moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_
   a.xcd_regions = static_cast<uint32_t>(p->xcd_regions);
   a.n_tensors = h.n_tensors;
   a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
-  a.paired = replay_paired(p) ? 1u : 0u;
+  a.paired = pair_log2(p);
   a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
   a.lr = adam->lr;
   a.beta1 = adam->beta1;
@@ -707,7 +712,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles
   uint64_t bound = 0;
   for (uint32_t t = 0; t < h.n_tensors; ++t)
-    if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t]) : tiles_of(h.tensors[t].numel, a.tile_elems);
+    if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t], a.paired) : tiles_of(h.tensors[t].numel, a.tile_elems);
   if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "replay: too many tiles for one launch");
   return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound), fused_slot, d_packed, s);
 }
@@ -920,7 +925,10 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
       p->plain_divide_sqrt = value ? 1 : 0;
       break;
     case MOEV_TUNE_PAIRED_TILES:
-      p->paired_tiles = value ? 1 : 0;
+      if (value == 1) value = 32768;
+      if (value != 0 && (value < 512 || value > (4 << 20) || (value & (value - 1))))
+        return fail(MOEV_E_INVAL, "the piece distance of the paired tiles is 0 (off), 1 (default) or a power of two in [512, 4 MiB]");
+      p->paired_tiles = value;
       break;
     case MOEV_TUNE_COPY_THREADS:
       if (!moev::direct_shape_supported(static_cast<uint32_t>(value), static_cast<uint32_t>(p->copy_unroll)))
@@ -1068,10 +1076,18 @@ int moev_copy_probe(void* d_dst, const void* d_src, size_t nbytes, uint32_t bloc
 }
 
 int moev_stream_probe(int mode, void* d_dst, const void* d_src, size_t nbytes, uint32_t value, int nontemporal, void* stream) {
-  if (mode != 1 && mode != 2) return fail(MOEV_E_INVAL, "moev_stream_probe: mode must be 1 (read only) or 2 (write only)");
-  if (!d_dst || (mode == 1 && !d_src) || nbytes == 0 || (nbytes & 15u))
+  if (mode < 1 || mode > 3) return fail(MOEV_E_INVAL, "moev_stream_probe: mode must be 1 (read only), 2 (write only) or 3 (paired copy)");
+  if (!d_dst || (mode != 2 && !d_src) || nbytes == 0 || (nbytes & 15u))
     return fail(MOEV_E_INVAL, "moev_stream_probe: null pointer or size not a multiple of 16");
-  if (!aligned16(d_dst) || (mode == 1 && !aligned16(d_src))) return fail(MOEV_E_INVAL, "moev_stream_probe: pointers must be 16-byte aligned");
+  if (!aligned16(d_dst) || (mode != 2 && !aligned16(d_src))) return fail(MOEV_E_INVAL, "moev_stream_probe: pointers must be 16-byte aligned");
+  if (mode == 3) {  // value = distance between the two pieces of a wavefront, a power of two in [512, 2^30]
+    if (value < 512 || value > (1u << 30) || (value & (value - 1)))
+      return fail(MOEV_E_INVAL, "moev_stream_probe: the piece distance must be a power of two in [512, 2^30]");
+    const uint64_t block = 2ull * value;
+    if (nbytes % block || reinterpret_cast<uintptr_t>(d_dst) % block || reinterpret_cast<uintptr_t>(d_src) % block)
+      return fail(MOEV_E_INVAL, "moev_stream_probe: paired copy needs size and pointers aligned to twice the piece distance");
+    value = static_cast<uint32_t>(__builtin_ctz(value));
+  }
   if ((nbytes + 4095) / 4096 >= (1ull << 31)) return fail(MOEV_E_RANGE, "moev_stream_probe: too large");
   MOEV_HIP(moev::launch_stream_probe(mode, d_src, d_dst, nbytes, value, nontemporal != 0, static_cast<hipStream_t>(stream)));
   return MOEV_OK;
@@ -1218,7 +1234,7 @@ int convert_replay_static(moev_plan* p, const moev_adam* adam, const uint8_t* d_
   uint64_t bound = p->tensor_tiles;
   if (a.paired) {
     bound = 0;
-    for (const auto& t : h.tensors) bound += paired_tiles_bound(t.numel);
+    for (const auto& t : h.tensors) bound += paired_tiles_bound(t.numel, a.paired);
     if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "convert_replay_static: too many tiles for one launch");
   }
   return launch_replay_direct(p, a, adam, d_scratch, direct_grid(bound), -1, nullptr, s);

@@ -293,6 +293,22 @@ __global__ __launch_bounds__(kThreads) void k_write_probe(uint8_t* __restrict__ 
 
 }  // namespace
 
+// Copy in which every wavefront instruction covers two 512-byte pieces 2^dist_log2 bytes apart (512: 1 KB of consecutive
+// bytes; 32768: the geometry of the replay's paired tiles).  The buffers are cut into blocks of twice that distance; wave
+// w of a block takes bytes [512 w, 512 w + 512) of both halves.  Pointers aligned to the block size, so the pieces of a
+// pair differ in that one address bit.
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_pair_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                         uint64_t nbytes, uint32_t dist_log2) {
+  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+  const uint32_t lane = threadIdx.x & 63;
+  const uint64_t per_block = 1ull << (dist_log2 - 9);
+  const uint64_t o = (wave / per_block) * (2ull << dist_log2) + (static_cast<uint64_t>(lane >> 5) << dist_log2) +
+                     (wave % per_block) * 512 + (lane & 31) * kVec;
+  if (o + kVec > nbytes) return;
+  st<NT>(reinterpret_cast<u32x4*>(dst + o), ld<NT>(reinterpret_cast<const u32x4*>(src + o)));
+}
+
 // ------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------
@@ -301,7 +317,10 @@ hipError_t launch_stream_probe(int mode, const void* src, void* dst, uint64_t nb
   const uint32_t blocks = static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec));
   const uint8_t* sp = static_cast<const uint8_t*>(src);
   uint8_t* dp = static_cast<uint8_t*>(dst);
-  if (mode == 1) {
+  if (mode == 3) {   // value = log2 of the distance between the two pieces of a wavefront
+    if (nontemporal) hipLaunchKernelGGL(k_pair_probe<true>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, value);
+    else hipLaunchKernelGGL(k_pair_probe<false>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, value);
+  } else if (mode == 1) {
     if (nontemporal) hipLaunchKernelGGL(k_read_probe<true>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes);
     else hipLaunchKernelGGL(k_read_probe<false>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes);
   } else {

@@ -61,7 +61,8 @@ struct AdamArgs {
   uint64_t header[7];
   uint32_t n_tensors, tile_elems, lds_entries, has_decay;
   uint32_t xcd_regions;        // as in CopyArgs
-  uint32_t paired;             // FP32 regime, 64 x 1 shape: paired tiles (two 512-byte pieces 32 KiB apart per stream and wavefront)
+  uint32_t paired;             // FP32 regime, 64 x 1 shape: paired tiles (two 512-byte pieces 2^paired ELEMENTS apart per stream
+                               // and wavefront; 13 = 32 KiB), 0 = consecutive tiles
   // state stored in other formats than FP32 / FP32 / FP32 / BF16 (k_adam_lp only)
   const float* scales;         // [4 * n_tensors] kind-major per-tensor scales, or null = all 1
   uint32_t fmt[4];             // kFmt* of master, m, v, compute
@@ -109,8 +110,6 @@ hipError_t launch_adam_persistent(const AdamArgs& a, uint32_t blocks, bool nt, h
 // storage formats (same values as the C interface's MOEV_FMT_*)
 constexpr uint32_t kFmtF32 = 1, kFmtF16 = 2, kFmtBF16 = 3, kFmtE4M3 = 4, kFmtE5M2 = 5;
 
-// paired tiles of the replay: a block of 16384 FP32 elements (64 KiB) holds 64 tiles of 2 x 128 elements
-constexpr uint32_t kPairedBlockElems = 16384, kPairedTilesPerBlock = 64;
 
 constexpr uint32_t kThreads = 256;           // 4 wavefronts of 64
 constexpr uint32_t kMaxLdsEntries = 8192;    // 32 KB of tile_start in LDS at most; larger tables are searched in global memory

@@ -562,7 +562,7 @@ def test_host_side_argument_checks(dev):
 
 
 def test_measurement_probes_move_what_they_say(dev):
-    """The copy / read-only / write-only probes (the yardsticks of bench.py): the copy is exact including a ragged
+    """The copy / read-only / write-only / paired-copy probes (the yardsticks of bench.py): the copy is exact including a ragged
     last tile, the write probe fills exactly its range, the read probe leaves its sink alone, bad arguments are refused."""
     n = (1 << 20) + 4096 + 48
     src = torch.randint(0, 255, (n + 64,), dtype=torch.uint8, device=dev)
@@ -581,7 +581,21 @@ def test_measurement_probes_move_what_they_say(dev):
     B.moev_stream_probe(1, dst, src, n, 0, 1)
     torch.cuda.synchronize()
     assert bool((dst == 0xEE).all())
-    for bad in (lambda: B.moev_stream_probe(3, dst, src, n), lambda: B.moev_stream_probe(1, dst, src, n + 1),
+    # paired copy: two 512-byte pieces per wavefront instruction, `value` bytes apart; blocks of twice that, aligned
+    arena_s = torch.randint(0, 255, ((1 << 20) * 3,), dtype=torch.uint8, device=dev)
+    arena_d = torch.full(((1 << 20) * 3,), 0xEE, dtype=torch.uint8, device=dev)
+    bs, bd = (-arena_s.data_ptr()) % (1 << 20), (-arena_d.data_ptr()) % (1 << 20)
+    for dist, size in ((512, 5 * 1024), (32768, 1 << 20), (32768, 3 << 16), (1 << 19, 1 << 20)):
+        arena_d.fill_(0xEE)
+        B.moev_stream_probe(3, arena_d[bd:], arena_s[bs:], size, dist, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(arena_d[bd:bd + size], arena_s[bs:bs + size]), (dist, size)
+        assert bool((arena_d[:bd] == 0xEE).all()) and bool((arena_d[bd + size:] == 0xEE).all())
+    for bad in (lambda: B.moev_stream_probe(4, dst, src, n), lambda: B.moev_stream_probe(1, dst, src, n + 1),
+                lambda: B.moev_stream_probe(3, arena_d[bd:], arena_s[bs:], 1 << 20, 3000),
+                lambda: B.moev_stream_probe(3, arena_d[bd:], arena_s[bs:], 1 << 20, 256),
+                lambda: B.moev_stream_probe(3, arena_d[bd:], arena_s[bs:], (1 << 20) + 4096, 32768),
+                lambda: B.moev_stream_probe(3, arena_d[bd + 4096:], arena_s[bs:], 1 << 16, 32768),
                 lambda: B.moev_stream_probe(1, dst, None, n), lambda: B.moev_stream_probe(2, dst[1:], None, n)):
         with pytest.raises(B.MoevError) as e:
             bad()
@@ -813,10 +827,12 @@ def test_window_with_consecutive_tiles(orc, dev, fused):
     assert rebuilt.guards_intact()
 
 
-def test_paired_tiles_cover_every_element_for_any_pointer_alignment(orc, dev):
+@pytest.mark.parametrize("distance", [None, 512, 2048, 65536, 1 << 20], ids=["default_32KiB", "512B", "2KiB", "64KiB", "1MiB"])
+def test_paired_tiles_cover_every_element_for_any_pointer_alignment(orc, dev, distance):
     """The paired tile grid follows the address of the master weights: tensors of block-multiple and ragged lengths at
     every kind of offset inside a 64 KiB block (0, 16 bytes, just below 32 KiB, just above, just below 64 KiB), with the
-    other streams at other offsets: every element is updated exactly once, nothing outside is touched."""
+    other streams at other offsets: every element is updated exactly once, nothing outside is touched.  Also for the
+    other piece distances the knob accepts (they exist for sweeps)."""
     lengths = [16384 * 3, 16384 * 2 + 8192, 16384 + 1, 8191, 257, 3, 40000, 1]
     offsets = [0, 16, 32768 - 16, 32768 + 512, 65536 - 16, 4096, 16384, 49152 + 48]
     wl = W.Workload("aligned", [(e, n) for e, n in enumerate(lengths)], [0] * len(lengths), 1)
@@ -842,8 +858,12 @@ def test_paired_tiles_cover_every_element_for_any_pointer_alignment(orc, dev):
                 views.setdefault("grad", []).append(view)
             else:
                 views[kind].append(view)
-    plan = make_plan(wl)
-    assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == 1
+    plan = make_plan(wl, paired=distance)
+    assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == (distance or 32768)
+    for bad in (3, 256, 48 * 1024, 8 << 20, -4):
+        with pytest.raises(B.MoevError) as e:
+            B.moev_tune(plan, B.TUNE_PAIRED_TILES, bad)
+        assert e.value.code == B.E_INVAL
     mask = torch.ones(wl.n_ops, dtype=torch.uint8, device=dev)
     B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, 11, mask, views["grad"],
                      B.State(*[views[k] for k in KINDS]))
