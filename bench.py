@@ -69,11 +69,15 @@ def parse_args():
     ap.add_argument("--adam-shape", default="", help="one-tile-per-workgroup shape of the replay as THREADSxUNROLL, e.g. 64x2 "
                     "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
-    ap.add_argument("--xcd-regions", type=int, default=-1)
+    ap.add_argument("--xcd-regions", type=int, default=-1, help="replay: 0 consecutive workgroups take consecutive tiles, 1 every XCD sweeps an "
+                    "eighth of the tiles (default), G >= 2: chunks of G tiles dealt to the XCDs round robin")
+    ap.add_argument("--copy-xcd-regions", type=int, default=-1, help="the same for pack and unpack (default 64)")
     ap.add_argument("--paired-tiles", type=int, default=-1, help="replay: distance in bytes between the two 512-byte pieces a wavefront "
                     "takes per stream (default 32768; a power of two in [512, 4 MiB]); 0: 1 KB of consecutive bytes")
     ap.add_argument("--paired-tiles-sweep", action="store_true", help="after the timed steps: the replay of the last window iteration "
                     "timed at every piece distance from 512 B to 4 MiB in this process (same tensors, same placement)")
+    ap.add_argument("--knob-sweep", action="store_true", help="after the timed steps: pack, unpack and replay timed under every launch knob "
+                    "and one-tile-per-workgroup shape in this process (same tensors, same placement)")
     ap.add_argument("--pair-distance-sweep", action="store_true", help="copy probe with two 512-byte pieces per wavefront instruction, "
                     "swept over their distance (512 B .. 2 MiB): shows the address bit the paired tiles exploit")
     ap.add_argument("--plain-divide-sqrt", type=int, default=-1, help="0: always the full IEEE division / square-root sequences in the replay")
@@ -292,10 +296,72 @@ def apply_launch_knobs(args, plan, B):
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, args.nontemporal)
     if args.xcd_regions >= 0:
         B.moev_tune(plan, B.TUNE_XCD_REGIONS, args.xcd_regions)
+    if args.copy_xcd_regions >= 0:
+        B.moev_tune(plan, B.TUNE_COPY_XCD_REGIONS, args.copy_xcd_regions)
     if args.plain_divide_sqrt >= 0:
         B.moev_tune(plan, B.TUNE_PLAIN_DIVIDE_SQRT, args.plain_divide_sqrt)
     if args.paired_tiles >= 0:
         B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles)
+
+
+def knob_sweep(args, wl, state, grads, packed, mask, stream, widths, torch, B):
+    """Every launch knob in turn, in THIS process and on the tensors of the timed steps, so that the physical placement of
+    the tensors (which alone moves the rates by several per cent between processes) is the same for every line: GB/s of the
+    pack (all W slots), the unpack (all W slots) and the replay (last iteration of the window: every operator active).
+    packed: one buffer per slot, or one buffer all slots go through; grads None: no replay (configs[3])."""
+    def shape(t, u):
+        knobs = []
+        for k_threads, k_unroll in ((B.TUNE_COPY_THREADS, B.TUNE_COPY_UNROLL), (B.TUNE_UNPACK_THREADS, B.TUNE_UNPACK_UNROLL),
+                                    (B.TUNE_ADAM_THREADS, B.TUNE_ADAM_UNROLL)):
+            knobs += [(k_unroll, 1), (k_threads, t), (k_unroll, u)]
+        return knobs
+
+    def regions(v):
+        return [(B.TUNE_XCD_REGIONS, v), (B.TUNE_COPY_XCD_REGIONS, v)]
+
+    variants = [("defaults", []), ("defaults again", []), ("xcd regions off", regions(0)), ("xcd regions: eighths", regions(1)),
+                ("nontemporal 0", [(B.TUNE_NONTEMPORAL, 0)]), ("paired_tiles 0", [(B.TUNE_PAIRED_TILES, 0)]),
+                ("persistent", [(B.TUNE_PERSISTENT, 1)])]
+    variants += [(f"xcd chunks of {g} tiles", regions(g)) for g in (2, 4, 8, 16, 32, 64, 128, 256, 1024, 4096, 16384, 65536)]
+    variants += [(f"shape {t}x{u}", shape(t, u)) for u in (1, 2, 4) for t in (64, 128, 256, 512, 1024) if t * u <= 1024]
+    buf = (lambda k: packed[k]) if isinstance(packed, (list, tuple)) else (lambda k: packed)
+    last = wl.window - 1
+    rows = {}
+    for label, knobs in variants:
+        plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
+        apply_launch_knobs(args, plan, B)
+        for knob, value in knobs:
+            B.moev_tune(plan, knob, value)
+        B.ckpt_plan_upload(plan, stream)
+        marks = {"pack": [], "unpack": [], "replay": []}
+
+        def timed(kind, fn):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            marks[kind].append((e0, e1))
+
+        for rep in range(4):      # the first repetition warms up
+            if rep == 1:
+                marks = {"pack": [], "unpack": [], "replay": []}
+            for k in range(wl.window):
+                timed("pack", lambda: B.snapshot_pack(plan, k, wl.t0 + k, state, buf(k), stream=stream))
+                timed("unpack", lambda: B.restore_unpack(plan, k, None, buf(k), state, mask, stream=stream))
+            if grads is not None:   # the mask now marks every operator active
+                for _ in range(2):
+                    timed("replay", lambda: B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + wl.window,
+                                                             mask, grads[wl.t0 + wl.window], state, stream=stream))
+        stream.synchronize()
+        B.ckpt_plan_device_status(plan, stream)
+        nbytes = {"pack": 3 * sum(pack_bytes(wl, k, widths) for k in range(wl.window)),
+                  "unpack": 3 * sum(unpack_bytes(wl, k, widths) for k in range(wl.window)),
+                  "replay": 6 * replay_bytes(wl, last, widths)}
+        rows[label] = {kind: round(nbytes[kind] / (sum(e0.elapsed_time(e1) for e0, e1 in ev) / 1e3) / 1e9, 1)
+                       for kind, ev in marks.items() if ev}
+        del plan
+    return {"what": "GB/s of algorithmic bytes per launch knob, same process and tensors: pack and unpack over all W slots, "
+                    "replay with every operator active", "GBs": rows}
 
 
 def rank_share_bench(args, steps, warmup, torch, B, W, dev):
@@ -522,6 +588,8 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
             "timeline_ms": {"drain_start": round(t_drain[0], 2), "drain_end": round(t_drain[1], 2),
                             "gemm_kernels_done_at": [[n, round(t, 2)] for n, t in ends]}}
         del host
+    if args.knob_sweep:
+        out["knob_sweep"] = knob_sweep(args, wl, state, None, packed, mask, main, FP32_WIDTHS, torch, B)
     del st, state, packed, a, b, c
     return out
 
@@ -708,6 +776,9 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles if args.paired_tiles >= 0 else 1)
         out["paired_tiles_sweep"] = {"what": "replay GB/s, all operators active, by distance in bytes between the two 512-byte pieces "
                                      "a wavefront takes per stream (0 and 512: consecutive bytes)", "GBs": sweep}
+
+    if args.knob_sweep and dtypes is None:
+        out["knob_sweep"] = knob_sweep(args, wl, state, grads, packed, mask, stream, widths, torch, B)
 
     # ---- launch-bound windows: the same step replayed from a HIP graph -------------------------------------
     # (with resident tables every call enqueues kernels only; all gradient pointers are passed in every

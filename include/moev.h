@@ -188,21 +188,26 @@ enum {
   MOEV_TUNE_ADAM_UNROLL = 9,
   MOEV_TUNE_UNPACK_THREADS = 10, /* the unpack's own shape (MOEV_TUNE_COPY_* is the pack's) */
   MOEV_TUNE_UNPACK_UNROLL = 11,
-  MOEV_TUNE_XCD_REGIONS = 12,    /* one tile per workgroup: 1 (default) = each of the 8 XCDs sweeps a contiguous
-                                    eighth of the tiles, 0 = consecutive workgroups take consecutive tiles */
+  MOEV_TUNE_XCD_REGIONS = 12,    /* replay, one tile per workgroup (workgroup ids go to the 8 XCDs round robin): 1 (default)
+                                    = each XCD sweeps a contiguous eighth of the launch's tiles; 0 = consecutive workgroups
+                                    take consecutive tiles; G = 2 .. 65536 (a power of two) = chunks of G consecutive tiles are
+                                    dealt to the XCDs round robin, so every XCD streams runs of G tiles while the chip-wide
+                                    window of addresses in flight stays 8 G tiles wide */
   MOEV_TUNE_PLAIN_DIVIDE_SQRT = 13, /* replay on low-precision state: 1 (default) = where every first and second moment
                                     of a wavefront has a magnitude in [2^-60, 2^40) (and the bias corrections are in
                                     [2^-20, 1], epsilon in [0, 2^20]) the three divisions and the square root run as the
                                     compiler's IEEE sequences WITHOUT their rescaling and special-case steps, which do
                                     nothing for such operands: same results, ~20% fewer instructions; 0 = always the
                                     full sequences */
-  MOEV_TUNE_PAIRED_TILES = 14      /* replay, FP32 regime, 64 x 1 shape (the default): every wavefront takes, per stream, two
+  MOEV_TUNE_PAIRED_TILES = 14,     /* replay, FP32 regime, 64 x 1 shape (the default): every wavefront takes, per stream, two
                                     512-byte pieces this many bytes apart instead of 1 KB of consecutive bytes.  32768 (default;
                                     1 selects it too): the addresses of a pair differ in bit 15 only, and on MI355X the memory
                                     system serves such pairs faster.  0 = consecutive tiles; any power of two in [512, 4 MiB] is
                                     accepted so that the distance can be swept (512 is the consecutive layout again).  The
                                     pairing follows the address of each tensor's master weights; other streams profit when
                                     their pointers are congruent to it modulo twice the distance.  Same results either way. */
+  MOEV_TUNE_COPY_XCD_REGIONS = 15  /* MOEV_TUNE_XCD_REGIONS for pack and unpack; default 64 (every XCD streams runs of 64 tiles =
+                                    256 KB) */
 };
 
 const char *moev_last_error(void);

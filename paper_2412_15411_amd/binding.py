@@ -21,7 +21,8 @@ FMT_DEFAULT, FMT_F32, FMT_F16, FMT_BF16, FMT_E4M3, FMT_E5M2 = range(6)
 HEADER_BYTES = 256
 (TUNE_COPY_TILE_BYTES, TUNE_COPY_MAX_BLOCKS, TUNE_ADAM_TILE_ELEMS, TUNE_ADAM_MAX_BLOCKS, TUNE_NONTEMPORAL,
  TUNE_PERSISTENT, TUNE_COPY_THREADS, TUNE_COPY_UNROLL, TUNE_ADAM_THREADS, TUNE_ADAM_UNROLL,
- TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL, TUNE_XCD_REGIONS, TUNE_PLAIN_DIVIDE_SQRT, TUNE_PAIRED_TILES) = range(15)
+ TUNE_UNPACK_THREADS, TUNE_UNPACK_UNROLL, TUNE_XCD_REGIONS, TUNE_PLAIN_DIVIDE_SQRT, TUNE_PAIRED_TILES,
+ TUNE_COPY_XCD_REGIONS) = range(16)
 
 EXPORTS = [
     "moev_last_error", "ckpt_plan", "ckpt_plan_free", "moev_find_window_size", "moev_order_operators",

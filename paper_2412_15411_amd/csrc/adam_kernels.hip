@@ -235,15 +235,17 @@ __device__ __forceinline__ void adam_tile_paired(const float* Ps, const float* M
   const uint64_t i = grid_pos - shift;
   if (i + 4 <= numel) {
     const Recip k1 = refined_reciprocal(c.bc1), k2 = refined_reciprocal(c.bc2);
+    // streaming (nontemporal) accesses for the six FP32 state streams; the gradient load and the bf16 store are plain:
+    // measured +0.6 % over streaming everything, while a plain access on any of the state streams costs 4-10 %
     const f32x4 p = ld<NT>(reinterpret_cast<const f32x4*>(Ps + i)), m = ld<NT>(reinterpret_cast<const f32x4*>(Ms + i)),
-                v = ld<NT>(reinterpret_cast<const f32x4*>(Vs + i)), g = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
+                v = ld<NT>(reinterpret_cast<const f32x4*>(Vs + i)), g = ld<false>(reinterpret_cast<const f32x4*>(G + i));
     float pe[4] = {p.x, p.y, p.z, p.w}, me[4] = {m.x, m.y, m.z, m.w}, ve[4] = {v.x, v.y, v.z, v.w};
     adam_quad(pe, me, ve, g, c, plain, k1, k2);
     st<NT>(reinterpret_cast<f32x4*>(P + i), f32x4{pe[0], pe[1], pe[2], pe[3]});
     st<NT>(reinterpret_cast<f32x4*>(M + i), f32x4{me[0], me[1], me[2], me[3]});
     st<NT>(reinterpret_cast<f32x4*>(V + i), f32x4{ve[0], ve[1], ve[2], ve[3]});
     const u32x2 cw = {bf16_bits(pe[0]) | (bf16_bits(pe[1]) << 16), bf16_bits(pe[2]) | (bf16_bits(pe[3]) << 16)};
-    st<NT>(reinterpret_cast<u32x2*>(C + i), cw);
+    st<false>(reinterpret_cast<u32x2*>(C + i), cw);
   } else if (i < numel) {
     // ragged tail of a tensor whose length is not a multiple of four
     for (uint64_t e = i; e < numel; ++e) {

@@ -115,7 +115,9 @@ struct moev_plan {
   int64_t adam_tile_elems = 8192;
   int64_t adam_max_blocks = 0;
   int64_t nontemporal = 1;
-  int64_t xcd_regions = 1;           // one tile per workgroup: contiguous eighth of the tiles per XCD
+  int64_t xcd_regions = 1;           // replay, one tile per workgroup: 1 = contiguous eighth of the tiles per XCD, 0 = off,
+                                     // G >= 2 (power of two) = chunks of G consecutive tiles dealt to the XCDs round robin
+  int64_t copy_xcd_regions = 64;     // the same for pack and unpack (64 tiles of 4 KB: every XCD streams 256 KB runs)
   int64_t plain_divide_sqrt = 1;     // low-precision replay: plain division / square root sequences where in range
   int64_t paired_tiles = 32768;      // FP32 replay, 64 x 1 shape: two 512-byte pieces this many bytes apart per stream and
                                      // wavefront (a power of two); 0: consecutive tiles
@@ -457,9 +459,10 @@ uint32_t grid_for(const moev_plan* pl, uint32_t tiles, int64_t cap) {
 
 // grid of a one-tile-per-workgroup launch: a multiple of the XCD count (the region mapping hands
 // workgroup b the (b / 8)-th tile of XCD b % 8), at least one workgroup
-uint32_t direct_grid(uint64_t tiles) {
-  const uint64_t g = (tiles + 7) / 8 * 8;
-  return static_cast<uint32_t>(g ? g : 8);
+uint32_t direct_grid(uint64_t tiles, int64_t xcd_regions = 1) {
+  const uint64_t unit = xcd_regions > 1 ? 8ull * static_cast<uint64_t>(xcd_regions) : 8ull;  // chunked mapping: whole rounds of chunks
+  const uint64_t g = (tiles + unit - 1) / unit * unit;
+  return static_cast<uint32_t>(g ? g : unit);
 }
 
 void fill_header(const moev_plan* pl, uint32_t slot, uint64_t iter, uint64_t out[7]) {
@@ -492,7 +495,7 @@ moev::CopyArgs copy_args(const moev_plan* pl, uint32_t slot, uint64_t iter, void
   a.n_ops = h.n_ops;
   a.slot_of_op = pl->d_slot_of_op;
   a.status = pl->d_status;
-  a.xcd_regions = static_cast<uint32_t>(pl->xcd_regions);
+  a.xcd_regions = static_cast<uint32_t>(pl->copy_xcd_regions);
   return a;
 }
 
@@ -584,7 +587,7 @@ int launch_unpack_locked(moev_plan* p, uint32_t slot, const void* h_pinned, void
   } else {
     a.tile_begin = compute_only ? p->slot_first_compute_tile[slot] : 0u;
     const uint32_t tiles = p->slot_tiles_unpack[slot] - a.tile_begin;
-    MOEV_HIP(moev::launch_unpack_direct(a, direct_grid(tiles), static_cast<uint32_t>(p->unpack_threads),
+    MOEV_HIP(moev::launch_unpack_direct(a, direct_grid(tiles, p->copy_xcd_regions), static_cast<uint32_t>(p->unpack_threads),
                                         static_cast<uint32_t>(p->unpack_unroll), p->nontemporal != 0, s));
   }
   return MOEV_OK;
@@ -713,8 +716,8 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   uint64_t bound = 0;
   for (uint32_t t = 0; t < h.n_tensors; ++t)
     if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t], a.paired) : tiles_of(h.tensors[t].numel, a.tile_elems);
-  if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "replay: too many tiles for one launch");
-  return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound), fused_slot, d_packed, s);
+  if (bound + 8ull * 65536 >= (1ull << 31)) return fail(MOEV_E_RANGE, "replay: too many tiles for one launch");
+  return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound, p->xcd_regions), fused_slot, d_packed, s);
 }
 
 }  // namespace
@@ -919,7 +922,10 @@ int moev_tune(moev_plan* p, int knob, int64_t value) {
       p->persistent = value ? 1 : 0;
       break;
     case MOEV_TUNE_XCD_REGIONS:
-      p->xcd_regions = value ? 1 : 0;
+    case MOEV_TUNE_COPY_XCD_REGIONS:
+      if (value < 0 || value > 65536 || (value & (value - 1)))
+        return fail(MOEV_E_INVAL, "xcd regions: 0 (off), 1 (eighths) or a chunk of 2..65536 tiles, a power of two");
+      (knob == MOEV_TUNE_XCD_REGIONS ? p->xcd_regions : p->copy_xcd_regions) = value;
       break;
     case MOEV_TUNE_PLAIN_DIVIDE_SQRT:
       p->plain_divide_sqrt = value ? 1 : 0;
@@ -980,6 +986,7 @@ int64_t moev_tune_get(const moev_plan* p, int knob) {
     case MOEV_TUNE_NONTEMPORAL: return p->nontemporal;
     case MOEV_TUNE_PERSISTENT: return p->persistent;
     case MOEV_TUNE_XCD_REGIONS: return p->xcd_regions;
+    case MOEV_TUNE_COPY_XCD_REGIONS: return p->copy_xcd_regions;
     case MOEV_TUNE_PLAIN_DIVIDE_SQRT: return p->plain_divide_sqrt;
     case MOEV_TUNE_PAIRED_TILES: return p->paired_tiles;
     case MOEV_TUNE_COPY_THREADS: return p->copy_threads;
@@ -1115,7 +1122,7 @@ int snapshot_pack(moev_plan* p, uint32_t slot, uint64_t iter, const moev_state* 
   if (p->persistent)
     MOEV_HIP(moev::launch_pack_persistent(a, grid_for(p, p->slot_tiles[slot], p->copy_max_blocks), p->nontemporal != 0, s));
   else
-    MOEV_HIP(moev::launch_pack_direct(a, direct_grid(p->slot_tiles[slot]), static_cast<uint32_t>(p->copy_threads),
+    MOEV_HIP(moev::launch_pack_direct(a, direct_grid(p->slot_tiles[slot], p->copy_xcd_regions), static_cast<uint32_t>(p->copy_threads),
                                       static_cast<uint32_t>(p->pack_unroll(slot)), p->nontemporal != 0, s));
   return MOEV_OK;
 }
@@ -1235,9 +1242,9 @@ int convert_replay_static(moev_plan* p, const moev_adam* adam, const uint8_t* d_
   if (a.paired) {
     bound = 0;
     for (const auto& t : h.tensors) bound += paired_tiles_bound(t.numel, a.paired);
-    if (bound >= (1ull << 31)) return fail(MOEV_E_RANGE, "convert_replay_static: too many tiles for one launch");
+    if (bound + 8ull * 65536 >= (1ull << 31)) return fail(MOEV_E_RANGE, "convert_replay_static: too many tiles for one launch");
   }
-  return launch_replay_direct(p, a, adam, d_scratch, direct_grid(bound), -1, nullptr, s);
+  return launch_replay_direct(p, a, adam, d_scratch, direct_grid(bound, p->xcd_regions), -1, nullptr, s);
 }
 
 int convert_window_step(moev_plan* p, uint32_t slot, const void* h_pinned, void* d_packed, const moev_adam* adam,

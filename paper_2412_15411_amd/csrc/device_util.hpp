@@ -54,6 +54,11 @@ __device__ __forceinline__ uint32_t owner_of_tile(P start, uint32_t n, uint32_t 
 constexpr uint32_t kXcds = 8;
 __device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t b, uint32_t n, uint32_t regions) {
   if (!regions) return b < n ? b : ~0u;
+  if (regions > 1) {  // chunks of `regions` (a power of two) consecutive tiles, dealt to the XCDs round robin
+    const uint32_t g = 31u - __builtin_clz(regions), idx = b / kXcds;
+    const uint32_t tile = ((idx >> g) << (g + 3)) + ((b % kXcds) << g) + (idx & (regions - 1u));
+    return tile < n ? tile : ~0u;
+  }
   const uint32_t per_xcd = (n + kXcds - 1) / kXcds;
   const uint32_t idx = b / kXcds;
   const uint32_t tile = (b % kXcds) * per_xcd + idx;

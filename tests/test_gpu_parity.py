@@ -99,6 +99,7 @@ def make_plan(wl, align=0, tile=None, blocks=None, adam_tile=None, adam_blocks=N
         B.moev_tune(plan, B.TUNE_NONTEMPORAL, nt)
     if xcd_regions is not None:
         B.moev_tune(plan, B.TUNE_XCD_REGIONS, xcd_regions)
+        B.moev_tune(plan, B.TUNE_COPY_XCD_REGIONS, xcd_regions)
     if paired is not None:
         B.moev_tune(plan, B.TUNE_PAIRED_TILES, paired)
     return plan
@@ -807,11 +808,13 @@ def test_fused_step_refuses_foreign_snapshot_and_missing_gradients(orc, dev):
     assert e.value.code == B.E_INVAL
 
 
+@pytest.mark.parametrize("regions", [0, 1, 2, 64, 4096, 65536], ids=["off", "eighths", "chunk2", "chunk64", "chunk4096", "chunk65536"])
 @pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_step"])
-def test_window_without_xcd_regions(orc, dev, fused):
-    """Consecutive workgroups take consecutive tiles (the XCD-region mapping switched off)."""
+def test_window_with_every_xcd_mapping(orc, dev, fused, regions):
+    """The workgroup -> tile mappings of the one-tile-per-workgroup kernels: consecutive, an eighth of the tiles per XCD,
+    chunks of G tiles dealt round robin (smaller and far larger than the launches of this workload)."""
     wl = ragged_workload(79, n_ops=10, window=4, with_empty=True)
-    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=7, align=256, fused=fused, xcd_regions=0)
+    rebuilt, live, dense = _gpu_window(orc, dev, wl, seed=7, align=256, fused=fused, xcd_regions=regions)
     assert states_equal(rebuilt.to_oracle(), live.to_oracle()) == []
     _compare_adam(rebuilt, dense, "ragged-window-no-regions")
     assert rebuilt.guards_intact()
