@@ -756,13 +756,13 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         out["fused_conversion"] = measure_fused()
 
     # ---- the replay at every piece distance of the paired tiles, same process and tensors ---------------------
-    if args.paired_tiles_sweep and dtypes is None and not args.persistent:
+    if args.paired_tiles_sweep and not args.persistent:
         last = wl.window - 1   # every operator active (the mask is in that state after a window)
         sweep = {}
         for dist in [0] + [1 << b for b in range(9, 23)]:
             B.moev_tune(plan, B.TUNE_PAIRED_TILES, dist)
             run = lambda: B.convert_replay(plan, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay, wl.t0 + wl.window, mask,
-                                           grads[wl.t0 + wl.window], state, stream=stream)
+                                           grads[wl.t0 + wl.window], state, stream=stream, d_scales=d_scales)
             for _ in range(2):
                 run()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -774,8 +774,9 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
             sweep[str(dist)] = round(8 * replay_bytes(wl, last, widths) / (e0.elapsed_time(e1) / 1e3) / 1e9, 1)
         B.ckpt_plan_device_status(plan, stream)
         B.moev_tune(plan, B.TUNE_PAIRED_TILES, args.paired_tiles if args.paired_tiles >= 0 else 1)
-        out["paired_tiles_sweep"] = {"what": "replay GB/s, all operators active, by distance in bytes between the two 512-byte pieces "
-                                     "a wavefront takes per stream (0 and 512: consecutive bytes)", "GBs": sweep}
+        out["paired_tiles_sweep"] = {"what": "replay GB/s, all operators active, by distance in bytes (of an FP32 stream; narrower "
+                                     "streams proportionally less) between the two pieces of 128 elements a wavefront takes per "
+                                     "stream (0 and 512: consecutive bytes)", "GBs": sweep}
 
     if args.knob_sweep and dtypes is None:
         out["knob_sweep"] = knob_sweep(args, wl, state, grads, packed, mask, stream, widths, torch, B)

@@ -199,10 +199,12 @@ enum {
                                     compiler's IEEE sequences WITHOUT their rescaling and special-case steps, which do
                                     nothing for such operands: same results, ~20% fewer instructions; 0 = always the
                                     full sequences */
-  MOEV_TUNE_PAIRED_TILES = 14,     /* replay, FP32 regime, 64 x 1 shape (the default): every wavefront takes, per stream, two
-                                    512-byte pieces this many bytes apart instead of 1 KB of consecutive bytes.  32768 (default;
-                                    1 selects it too): the addresses of a pair differ in bit 15 only, and on MI355X the memory
-                                    system serves such pairs faster.  0 = consecutive tiles; any power of two in [512, 4 MiB] is
+  MOEV_TUNE_PAIRED_TILES = 14,     /* replay in its 64 x 1 shape (the default of the FP32 regime and of the regimes with more than 6
+                                    bytes of master weights and moments per parameter): every wavefront takes, per stream, two
+                                    pieces of 128 elements instead of 256 consecutive elements; the value is their distance in
+                                    bytes for an FP32 stream (narrower streams proportionally less).  32768 (default; 1 selects
+                                    it too): the addresses of a pair differ in bit 15 only, and on MI355X the memory system
+                                    serves such pairs faster.  0 = consecutive tiles; any power of two in [512, 4 MiB] is
                                     accepted so that the distance can be swept (512 is the consecutive layout again).  The
                                     pairing follows the address of each tensor's master weights; other streams profit when
                                     their pointers are congruent to it modulo twice the distance.  Same results either way. */

@@ -29,8 +29,16 @@ namespace {
 // for every other stream whose pointer is congruent to it modulo the block size (separately allocated
 // tensors usually are); positions below `shift` and beyond the tensor's end are idle lanes.
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t pair_shift(const void* master, uint32_t L) {
-  return (static_cast<uint32_t>(reinterpret_cast<uintptr_t>(master)) & ((8u << L) - 1u)) >> 2;
+// elements between the start of the address block (2^(L+1) elements of 2^wlog2 bytes) and the tensor's first element
+__device__ __forceinline__ uint32_t pair_shift(const void* master, uint32_t L, uint32_t wlog2) {
+  return (static_cast<uint32_t>(reinterpret_cast<uintptr_t>(master)) & (((2u << L) << wlog2) - 1u)) >> wlog2;
+}
+// first element of this lane's quad in paired tile `tile` of a tensor (tiles count from the tensor's first), or ~0 when
+// the quad lies in front of the tensor's first element
+__device__ __forceinline__ uint64_t paired_quad(uint32_t tile, uint32_t L, uint32_t shift) {
+  const uint64_t grid_pos = (static_cast<uint64_t>(tile >> (L - 7)) << (L + 1)) + (static_cast<uint64_t>(threadIdx.x >> 5) << L) +
+                            ((tile & ((1u << (L - 7)) - 1u)) << 7) + 4u * (threadIdx.x & 31u);
+  return grid_pos >= shift ? grid_pos - shift : ~0ull;  // shift and grid_pos are multiples of four
 }
 __device__ __forceinline__ uint64_t paired_tiles(uint64_t numel, uint32_t shift, uint32_t L) {
   return numel ? ((numel + shift + (2u << L) - 1) >> (L + 1)) << (L - 7) : 0;
@@ -50,7 +58,7 @@ __global__ __launch_bounds__(kThreads) void k_active_scan(const AdamArgs a, uint
       const bool active = a.mask[a.op_of_tensor[t]] != 0;
       const bool has_grad = a.grads[t] != nullptr;
       if (active && !has_grad && numel) *a.status = 2u;  // reported by the status query, tensor skipped
-      if (active && has_grad) tiles = a.paired ? paired_tiles(numel, pair_shift(a.ptrs[t], a.paired), a.paired) : (numel + a.tile_elems - 1) / a.tile_elems;
+      if (active && has_grad) tiles = a.paired ? paired_tiles(numel, pair_shift(a.ptrs[t], a.paired, a.master_wlog2), a.paired) : (numel + a.tile_elems - 1) / a.tile_elems;
     }
     uint64_t all;
     const uint64_t excl = block_exclusive_scan(tiles, lds, &all);
@@ -228,11 +236,8 @@ __device__ __forceinline__ void adam_tile_paired(const float* Ps, const float* M
                                                  const float* __restrict__ G, float* P, float* M, float* V,
                                                  uint16_t* __restrict__ C, uint64_t numel, uint32_t L, uint32_t tile,
                                                  const AdamConst& c, bool plain) {
-  const uint32_t shift = pair_shift(P, L);
-  const uint64_t grid_pos = (static_cast<uint64_t>(tile >> (L - 7)) << (L + 1)) + (static_cast<uint64_t>(threadIdx.x >> 5) << L) +
-                            ((tile & ((1u << (L - 7)) - 1u)) << 7) + 4u * (threadIdx.x & 31u);
-  if (grid_pos < shift) return;  // in front of the tensor's first element (shift and grid_pos are multiples of four)
-  const uint64_t i = grid_pos - shift;
+  const uint64_t i = paired_quad(tile, L, pair_shift(P, L, 2));
+  if (i == ~0ull) return;
   if (i + 4 <= numel) {
     const Recip k1 = refined_reciprocal(c.bc1), k2 = refined_reciprocal(c.bc2);
     // streaming (nontemporal) accesses for the six FP32 state streams; the gradient load and the bf16 store are plain:
@@ -518,59 +523,71 @@ __device__ __forceinline__ void store_first(uint8_t* base, uint64_t e, const typ
   st<false>(reinterpret_cast<One*>(base) + e, static_cast<One>(bits));
 }
 
+// The quads at elements pos[0..U) of one tensor (multiples of four; a position at or beyond `end` is skipped), in place.
+template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC, uint32_t U, bool NT>
+__device__ __forceinline__ void adam_lp_quads(uint8_t* P, uint8_t* M, uint8_t* V, const float* __restrict__ G,
+                                              uint8_t* __restrict__ C, const uint64_t (&pos)[U], uint64_t end, const LpScales& sc,
+                                              const AdamConst& c, bool fast, const Recip& k1, const Recip& k2) {
+  using QP = typename Fmt<FP>::Quad;
+  using QM = typename Fmt<FM>::Quad;
+  using QV = typename Fmt<FV>::Quad;
+  using QC = typename Fmt<FC>::Quad;
+  constexpr uint32_t WP = Fmt<FP>::kBytes, WM = Fmt<FM>::kBytes, WV = Fmt<FV>::kBytes, WC = Fmt<FC>::kBytes;
+  QP p[U];
+  QM m[U];
+  QV v[U];
+  f32x4 g[U];
+#pragma unroll
+  for (uint32_t u = 0; u < U; ++u) {
+    const uint64_t i = pos[u];
+    if (i < end && i + 4 <= end) {
+      p[u] = ld<NT>(reinterpret_cast<const QP*>(P + i * WP));
+      m[u] = ld<NT>(reinterpret_cast<const QM*>(M + i * WM));
+      v[u] = ld<NT>(reinterpret_cast<const QV*>(V + i * WV));
+      g[u] = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
+    }
+  }
+#pragma unroll
+  for (uint32_t u = 0; u < U; ++u) {
+    const uint64_t i = pos[u];
+    if (i >= end) continue;
+    if (i + 4 <= end) {
+      QC cw;
+      adam_lp_quad<FP, FM, FV, FC>(p[u], m[u], v[u], cw, g[u], sc, c, fast, k1, k2);
+      st<NT>(reinterpret_cast<QP*>(P + i * WP), p[u]);
+      st<NT>(reinterpret_cast<QM*>(M + i * WM), m[u]);
+      st<NT>(reinterpret_cast<QV*>(V + i * WV), v[u]);
+      st<NT>(reinterpret_cast<QC*>(C + i * WC), cw);
+    } else {
+      // ragged tail of a tensor whose length is not a multiple of four: one element at a time,
+      // in the first position of a quad
+      for (uint64_t e = i; e < end; ++e) {
+        QP p1 = quad_of_one<FP>(P, e);
+        QM m1 = quad_of_one<FM>(M, e);
+        QV v1 = quad_of_one<FV>(V, e);
+        QC c1;
+        const f32x4 g1 = {ld<false>(G + e), 0.0f, 0.0f, 0.0f};
+        adam_lp_quad<FP, FM, FV, FC>(p1, m1, v1, c1, g1, sc, c, false, k1, k2);
+        store_first<FP>(P, e, p1);
+        store_first<FM>(M, e, m1);
+        store_first<FV>(V, e, v1);
+        store_first<FC>(C, e, c1);
+      }
+    }
+  }
+}
+
 // Elements [begin, end) of one tensor, in place; begin is a multiple of four.
 template <uint32_t FP, uint32_t FM, uint32_t FV, uint32_t FC, uint32_t T, uint32_t U, bool NT>
 __device__ __forceinline__ void adam_lp_range(uint8_t* P, uint8_t* M, uint8_t* V, const float* __restrict__ G,
                                               uint8_t* __restrict__ C, uint64_t begin, uint64_t end, const LpScales& sc,
                                               const AdamConst& c, bool fast) {
   const Recip k1 = refined_reciprocal(c.bc1), k2 = refined_reciprocal(c.bc2);
-  using QP = typename Fmt<FP>::Quad;
-  using QM = typename Fmt<FM>::Quad;
-  using QV = typename Fmt<FV>::Quad;
-  using QC = typename Fmt<FC>::Quad;
-  constexpr uint32_t WP = Fmt<FP>::kBytes, WM = Fmt<FM>::kBytes, WV = Fmt<FV>::kBytes, WC = Fmt<FC>::kBytes;
   for (uint64_t base = begin + 4ull * threadIdx.x; base < end; base += 4ull * T * U) {
-    QP p[U];
-    QM m[U];
-    QV v[U];
-    f32x4 g[U];
+    uint64_t pos[U];
 #pragma unroll
-    for (uint32_t u = 0; u < U; ++u) {
-      const uint64_t i = base + 4ull * T * u;
-      if (i + 4 <= end) {
-        p[u] = ld<NT>(reinterpret_cast<const QP*>(P + i * WP));
-        m[u] = ld<NT>(reinterpret_cast<const QM*>(M + i * WM));
-        v[u] = ld<NT>(reinterpret_cast<const QV*>(V + i * WV));
-        g[u] = ld<NT>(reinterpret_cast<const f32x4*>(G + i));
-      }
-    }
-#pragma unroll
-    for (uint32_t u = 0; u < U; ++u) {
-      const uint64_t i = base + 4ull * T * u;
-      if (i + 4 <= end) {
-        QC cw;
-        adam_lp_quad<FP, FM, FV, FC>(p[u], m[u], v[u], cw, g[u], sc, c, fast, k1, k2);
-        st<NT>(reinterpret_cast<QP*>(P + i * WP), p[u]);
-        st<NT>(reinterpret_cast<QM*>(M + i * WM), m[u]);
-        st<NT>(reinterpret_cast<QV*>(V + i * WV), v[u]);
-        st<NT>(reinterpret_cast<QC*>(C + i * WC), cw);
-      } else if (i < end) {
-        // ragged tail of a tensor whose length is not a multiple of four: one element at a time,
-        // in the first position of a quad
-        for (uint64_t e = i; e < end; ++e) {
-          QP p1 = quad_of_one<FP>(P, e);
-          QM m1 = quad_of_one<FM>(M, e);
-          QV v1 = quad_of_one<FV>(V, e);
-          QC c1;
-          const f32x4 g1 = {ld<false>(G + e), 0.0f, 0.0f, 0.0f};
-          adam_lp_quad<FP, FM, FV, FC>(p1, m1, v1, c1, g1, sc, c, false, k1, k2);
-          store_first<FP>(P, e, p1);
-          store_first<FM>(M, e, m1);
-          store_first<FV>(V, e, v1);
-          store_first<FC>(C, e, c1);
-        }
-      }
-    }
+    for (uint32_t u = 0; u < U; ++u) pos[u] = base + 4ull * T * u;
+    adam_lp_quads<FP, FM, FV, FC, U, NT>(P, M, V, G, C, pos, end, sc, c, fast, k1, k2);
   }
 }
 
@@ -590,6 +607,20 @@ __global__ __launch_bounds__(T) void k_adam_lp(MOEV_ADAM_TABLES, const float* __
   for (uint32_t k = 0; k < 4; ++k) {
     sc.s[k] = scales ? scales[static_cast<uint64_t>(k) * a.n_tensors + t] : 1.0f;
     sc.inv[k] = 1.0f / sc.s[k];
+  }
+  if constexpr (T == 64 && U == 1) {
+    if (a.paired) {   // paired tile: this lane's quad of the tensor, see adam_tile_paired
+      uint8_t* P = static_cast<uint8_t*>(ptrs[t]);
+      constexpr uint32_t kMasterLog2 = Fmt<FP>::kBytes == 4 ? 2u : Fmt<FP>::kBytes == 2 ? 1u : 0u;
+      const uint64_t pos[1] = {paired_quad(tile - tile_start[t], a.paired, pair_shift(P, a.paired, kMasterLog2))};
+      if (pos[0] == ~0ull) return;
+      const AdamConst c = adam_const(a);
+      adam_lp_quads<FP, FM, FV, FC, 1, NT>(P, static_cast<uint8_t*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]),
+                                           static_cast<uint8_t*>(ptrs[2ull * a.n_tensors + t]), static_cast<const float*>(grads[t]),
+                                           static_cast<uint8_t*>(ptrs[3ull * a.n_tensors + t]), pos, numel, sc, c,
+                                           a.plain_divide_sqrt != 0, refined_reciprocal(c.bc1), refined_reciprocal(c.bc2));
+      return;
+    }
   }
   adam_lp_range<FP, FM, FV, FC, T, U, NT>(static_cast<uint8_t*>(ptrs[t]),
                                           static_cast<uint8_t*>(ptrs[static_cast<uint64_t>(a.n_tensors) + t]),

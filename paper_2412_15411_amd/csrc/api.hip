@@ -524,19 +524,25 @@ bool fp32_regime(const moev::HostPlan& h) {
   return h.fmt[MOEV_KIND_MASTER] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_ADAM_M] == MOEV_FMT_F32 &&
          h.fmt[MOEV_KIND_ADAM_V] == MOEV_FMT_F32 && h.fmt[MOEV_KIND_COMPUTE] == MOEV_FMT_BF16;
 }
-// paired tiles apply to the default one-tile-per-workgroup shape of the FP32 regime only
+// paired tiles apply to the default one-tile-per-workgroup shape only (master weights of 1, 2 or 4 bytes)
 bool replay_paired(const moev_plan* p) {
-  return p->paired_tiles && !p->persistent && p->adam_threads == 64 && p->adam_unroll == 1 && fp32_regime(p->host);
+  return p->paired_tiles && !p->persistent && p->adam_threads == 64 && p->adam_unroll == 1 && p->host.width[MOEV_KIND_MASTER] <= 4;
+}
+uint32_t master_wlog2(const moev_plan* p) {
+  const uint32_t w = p->host.width[MOEV_KIND_MASTER];
+  return w >= 4 ? 2u : w == 2 ? 1u : 0u;
 }
 
-// log2 of the piece distance in FP32 elements (the kernels' parameter), 0 when the replay is not paired
+// log2 of the piece distance in elements (the kernels' parameter; the knob is the distance in bytes of an FP32 stream, which
+// the gradients always are), 0 when the replay is not paired
 uint32_t pair_log2(const moev_plan* p) {
   return replay_paired(p) ? static_cast<uint32_t>(__builtin_ctzll(static_cast<uint64_t>(p->paired_tiles))) - 2u : 0u;
 }
 // tiles of one tensor under the paired shape; `master` locates the tensor inside its address block of 2^(L+1) elements
-uint64_t paired_tiles_of(uint64_t numel, const void* master, uint32_t L) {
+// of 2^wlog2 bytes
+uint64_t paired_tiles_of(uint64_t numel, const void* master, uint32_t L, uint32_t wlog2) {
   if (numel == 0) return 0;
-  const uint64_t shift = (reinterpret_cast<uintptr_t>(master) & ((8ull << L) - 1)) >> 2;
+  const uint64_t shift = (reinterpret_cast<uintptr_t>(master) & (((2ull << L) << wlog2) - 1)) >> wlog2;
   return ((numel + shift + (2ull << L) - 1) >> (L + 1)) << (L - 7);
 }
 // ... when the pointer is not known to the host: the largest shift a 16-byte aligned pointer can have
@@ -638,6 +644,7 @@ moev::AdamArgs adam_args(const moev_plan* p, const moev_adam* adam, const uint8_
   a.n_tensors = h.n_tensors;
   a.tile_elems = static_cast<uint32_t>(p->eff_adam_tile());
   a.paired = pair_log2(p);
+  a.master_wlog2 = master_wlog2(p);
   a.lds_entries = (p->persistent && h.n_tensors + 1 <= moev::kMaxLdsEntries) ? h.n_tensors + 1 : 0;
   a.lr = adam->lr;
   a.beta1 = adam->beta1;
@@ -715,7 +722,7 @@ int launch_replay_locked(moev_plan* p, const moev_adam* adam, const uint8_t* d_a
   // the host only bounds the grid: tensors without a gradient pointer cannot contribute tiles
   uint64_t bound = 0;
   for (uint32_t t = 0; t < h.n_tensors; ++t)
-    if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t], a.paired) : tiles_of(h.tensors[t].numel, a.tile_elems);
+    if (grads[t]) bound += a.paired ? paired_tiles_of(h.tensors[t].numel, state->master[t], a.paired, a.master_wlog2) : tiles_of(h.tensors[t].numel, a.tile_elems);
   if (bound + 8ull * 65536 >= (1ull << 31)) return fail(MOEV_E_RANGE, "replay: too many tiles for one launch");
   return launch_replay_direct(p, a, adam, p->d_active_tile_start, direct_grid(bound, p->xcd_regions), fused_slot, d_packed, s);
 }

@@ -61,8 +61,9 @@ struct AdamArgs {
   uint64_t header[7];
   uint32_t n_tensors, tile_elems, lds_entries, has_decay;
   uint32_t xcd_regions;        // as in CopyArgs
-  uint32_t paired;             // FP32 regime, 64 x 1 shape: paired tiles (two 512-byte pieces 2^paired ELEMENTS apart per stream
-                               // and wavefront; 13 = 32 KiB), 0 = consecutive tiles
+  uint32_t paired;             // 64 x 1 shape: paired tiles (per stream and wavefront two pieces of 128 elements, 2^paired ELEMENTS
+                               // apart; 13 = 32 KiB for FP32 streams), 0 = consecutive tiles
+  uint32_t master_wlog2;       // log2 of the bytes per master-weight element (the paired grid follows the master pointers)
   // state stored in other formats than FP32 / FP32 / FP32 / BF16 (k_adam_lp only)
   const float* scales;         // [4 * n_tensors] kind-major per-tensor scales, or null = all 1
   uint32_t fmt[4];             // kFmt* of master, m, v, compute

@@ -122,6 +122,28 @@ def test_low_precision_replay_matches_oracle(orc, dev, name):
                 assert after.kinds()[kind][t].tobytes() == start.kinds()[kind][t].tobytes()
 
 
+@pytest.mark.parametrize("distance", [0, 512, 16384, 65536, 1 << 20], ids=["consecutive", "512B", "16KiB", "64KiB", "1MiB"])
+@pytest.mark.parametrize("name", ["fp16_fp16_fp16+fp16", "fp8_fp16_fp32+fp32", "fp8_fp8_fp8+fp16"])
+def test_low_precision_replay_paired_tile_distances(orc, dev, name, distance):
+    """The paired tiles of the 64 x 1 shape (default distance: test_low_precision_replay_matches_oracle) at other piece
+    distances and switched off, with master weights of 2, 2 and 1 bytes: the tile grid follows the master pointers, which
+    sit at arbitrary 16-byte offsets in the arena."""
+    dtypes = REGIMES[name]
+    wl = ragged_workload(55, max_numel=70000)
+    table = scale_table(wl, dtypes, seed=3)
+    st_cpu = W.make_low_precision_state(wl, dtypes, [list(r) for r in table.tolist()], seed=5)
+    grads = W.make_grads(wl, 9, seed=5)
+    mask_np = np.ones(wl.n_ops, dtype=np.uint8)
+    mask_np[2] = 0
+    hp = orc.AdamHP(lr=1e-3, weight_decay=0.01)
+    plan = lp_plan(wl, dtypes)
+    assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == 32768
+    B.moev_tune(plan, B.TUNE_PAIRED_TILES, distance)
+    ds, ref, fmts = run_both(orc, dev, wl, dtypes, st_cpu, table, grads, mask_np, hp, 9, plan)
+    assert_states_match(orc, ds, ref, fmts)
+    assert ds.guards_intact()
+
+
 @pytest.mark.parametrize("shape", [(64, 2), (128, 1), (128, 2), (256, 1), (256, 2)])
 def test_low_precision_replay_launch_shapes(orc, dev, shape):
     dtypes = REGIMES["fp8_fp8_fp8+fp16"]
