@@ -48,9 +48,13 @@ __device__ __forceinline__ uint32_t owner_of_tile(P start, uint32_t n, uint32_t 
 }
 
 // Tile of workgroup `b` in a launch over `n` tiles.  Workgroup ids are handed to the 8 XCDs round
-// robin; with `regions` every XCD sweeps its own contiguous eighth of the tiles instead of every
-// eighth tile (each XCD then touches an eighth of the pages; ~2% more copy bandwidth).  Returns
-// ~0u for workgroups beyond the last tile.
+// robin, so with the plain mapping (regions 0) every XCD touches every eighth tile.  regions 1: every XCD
+// sweeps its own contiguous eighth of the tiles (the replay's default).  regions G >= 2, a power of two:
+// chunks of G consecutive tiles are dealt to the XCDs round robin, so every XCD streams runs of G tiles
+// while the chip-wide window of addresses in flight stays 8 G tiles wide (pack and unpack: G = 64); the
+// grid must then be a multiple of 8 G workgroups.  Measured in one process per workload: no mapping
+// loses 1-5 % on every kernel, eighths cost the unpack 3-6 % against chunks of 64 tiles, chunks of 4-16
+// tiles are the worst choice.  Returns ~0u for workgroups beyond the last tile.
 constexpr uint32_t kXcds = 8;
 __device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t b, uint32_t n, uint32_t regions) {
   if (!regions) return b < n ? b : ~0u;
