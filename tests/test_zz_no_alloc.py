@@ -96,6 +96,44 @@ def test_static_replay_equals_convert_replay_on_two_calls_in_a_row(orc, dev):
     print(f"static replay: worst relative error against the oracle {max(w1, w2, w3):.3g}")
 
 
+@pytest.mark.parametrize("regime", ["fp8_fp32_fp32+fp32", "fp8_fp16_fp32+fp32", "fp8_fp8_fp8+fp16"])
+def test_static_replay_on_low_precision_state(dev, regime):
+    """State stored in the formats of a low-precision regime (master weights of 4, 2 and 1 bytes; the first two run the
+    paired 64 x 1 shape, whose grid the static call sizes without knowing the pointers): same codes as convert_replay,
+    whose parity with the oracle the low-precision tests establish."""
+    from test_gpu_low_precision import LIB_FMT_OF_DTYPE
+    dtypes = W.LOW_PRECISION_REGIMES[regime]
+    wl = _workload(9, n_ops=12, max_numel=60000)
+    per_kind = W.default_scales(dtypes)
+    st_cpu = W.make_low_precision_state(wl, dtypes, per_kind, seed=4)
+    ref_state = {k: [t.to(dev) for t in st_cpu[k]] for k in KINDS}
+    new_state = {k: [t.to(dev) for t in st_cpu[k]] for k in KINDS}
+    d_scales = torch.tensor([[x] * wl.n_tensors for x in per_kind], dtype=torch.float32, device=dev)
+    active = [1 if s != 1 else 0 for s in wl.slot_of_op]
+    mask = torch.tensor(active, dtype=torch.uint8, device=dev)
+    formats = [LIB_FMT_OF_DTYPE[d] for d in dtypes]
+    plan_ref = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=formats)
+    plan_new = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=formats)
+    B.ckpt_plan_upload(plan_new)
+    state_table = _device_table([t for k in KINDS for t in new_state[k]], dev)
+    for step in (7, 8):
+        grads_cpu = W.make_grads(wl, step, seed=4)
+        grads = [g.to(dev) if active[wl.tensors[t][0]] else None for t, g in enumerate(grads_cpu)]
+        B.convert_replay(plan_ref, 1e-3, 0.9, 0.95, 1e-8, 0.01, step, mask, grads, B.State(*[ref_state[k] for k in KINDS]),
+                         d_scales=d_scales)
+        B.convert_replay_static(plan_new, 1e-3, 0.9, 0.95, 1e-8, 0.01, step, mask, _device_table(grads, dev), state_table,
+                                d_scales=d_scales)
+        torch.cuda.synchronize()
+    B.ckpt_plan_device_status(plan_ref)
+    B.ckpt_plan_device_status(plan_new)
+    changed = 0
+    for k in KINDS:
+        for t, (a, b) in enumerate(zip(ref_state[k], new_state[k])):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"{regime}: {k}[{t}] differs from convert_replay"
+            changed += int(b.numel() > 0 and not torch.equal(b.view(torch.uint8), st_cpu[k][t].to(dev).view(torch.uint8)))
+    assert changed > 0
+
+
 def test_static_replay_refuses_plans_beyond_its_scratch(dev):
     n = 65536 + 1
     plan = B.ckpt_plan([(e, 4) for e in range(n)], B.EXPLICIT, window=1, slot_of_op=[0] * n)
