@@ -107,6 +107,36 @@ def replay_bytes(wl, i, widths=FP32_WIDTHS):
     return (2 * (widths[0] + widths[1] + widths[2]) + 4 + widths[3]) * wl.active_params_at(i)
 
 
+def kernel_table(timings, wl, widths):
+    """timings: (kind, algorithmic bytes, start event, end event) of every timed launch, each kind in slot / iteration order
+    0 .. W-1 step after step.  -> ({kind: bytes, ms, launches}, the `kernels` object of the JSON line: per kind the rate of
+    algorithmic bytes over all launches, per slot (pack, unpack) or per replay iteration, and for the two copies the
+    payload rate (snapshot bytes / time: half of the pack's traffic))."""
+    per_kind, per_slot = {}, {}
+    for kind, nbytes, e0, e1 in timings:
+        ms = e0.elapsed_time(e1)
+        d = per_kind.setdefault(kind, {"bytes": 0, "ms": 0.0, "launches": 0})
+        slot = d["launches"] % wl.window
+        d["bytes"] += nbytes
+        d["ms"] += ms
+        d["launches"] += 1
+        ps = per_slot.setdefault(kind, [[0, 0.0] for _ in range(wl.window)])
+        ps[slot][0] += nbytes
+        ps[slot][1] += ms
+    kernels = {}
+    for kind, d in per_kind.items():
+        gbs = d["bytes"] / (d["ms"] / 1e3) / 1e9
+        kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
+                         "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"],
+                         ("per_iteration_GBs" if kind == "replay" else "per_slot_GBs"):
+                             [round(b / (ms / 1e3) / 1e9, 1) if ms else None for b, ms in per_slot[kind]]}
+        if kind in ("pack", "unpack"):
+            payload = sum(wl.slot_payload_bytes(k, widths) for k in range(wl.window)) * (d["launches"] // wl.window)
+            kernels[kind]["payload_GBs"] = round(payload / (d["ms"] / 1e3) / 1e9, 1)
+    return per_kind, kernels
+
+
 def read_valu_count(kernel, regime):
     """Vector-ALU instructions per parameter of a kernel, from the SQ_INSTS_VALU counter run summarised in
     profiles/valu_instructions.txt, or None."""
@@ -411,18 +441,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     B.ckpt_plan_device_status(plan, main)
-    per_kind = {}
-    for kind, nbytes, e0, e1 in timings:
-        d = per_kind.setdefault(kind, {"bytes": 0, "ms": 0.0, "launches": 0})
-        d["bytes"] += nbytes
-        d["ms"] += e0.elapsed_time(e1)
-        d["launches"] += 1
-    kernels = {}
-    for kind, d in per_kind.items():
-        gbs = d["bytes"] / (d["ms"] / 1e3) / 1e9
-        kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                         "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
-                         "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
+    per_kind, kernels = kernel_table(timings, wl, FP32_WIDTHS)
     value = step_bytes / (elapsed / steps) / 1e9
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
@@ -574,7 +593,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
         t_drain = (origin.elapsed_time(e0), origin.elapsed_time(e1))
         ends = [(n, origin.elapsed_time(ev)) for n, ev in marks]
         during = [(n, t) for n, t in ends if t_drain[0] <= t <= t_drain[1]]
-        out["drain"] = {"bound": "host-link", "slot": k, "bytes": nbytes, "ms": round(drain_alone_ms, 2),
+        out["drain"] = {"bound": "host-link", "link": "PCIe Gen5 x16, 64 GB/s per direction in theory", "slot": k, "bytes": nbytes, "ms": round(drain_alone_ms, 2),
                         "GBs": round(nbytes / (drain_alone_ms / 1e3) / 1e9, 2),
                         "header_ok": B.snapshot_peek(plan, k, host)["slot"] == k}
         out["drain_under_gemm"] = {
@@ -582,6 +601,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
             "drain_ms": round(t_drain[1] - t_drain[0], 2),
             "drain_GBs": round(nbytes / ((t_drain[1] - t_drain[0]) / 1e3) / 1e9, 2),
             "gemm_ms_alone": round(gemm_alone_ms, 2), "gemm_ms_with_drain": round(ends[-1][1], 2),
+            "gemm_slowdown_pct": round((ends[-1][1] / gemm_alone_ms - 1) * 100, 2),
             "gemm_us_per_kernel_alone": round(gemm_alone_ms / n_gemm * 1e3, 2),
             "gemm_us_per_kernel_while_draining": (round((during[-1][1] - during[0][1]) / (during[-1][0] - during[0][0]) * 1e3, 2)
                                                   if len(during) > 1 else None),
@@ -673,18 +693,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     value = step_bytes / (elapsed / steps) / 1e9
     per_step_ms = sorted(step_marks[n].elapsed_time(step_marks[n + 1]) for n in range(steps))
 
-    per_kind = {}
-    for kind, nbytes, e0, e1 in timings:
-        d = per_kind.setdefault(kind, {"bytes": 0, "ms": 0.0, "launches": 0})
-        d["bytes"] += nbytes
-        d["ms"] += e0.elapsed_time(e1)
-        d["launches"] += 1
-    kernels = {}
-    for kind, d in per_kind.items():
-        gbs = d["bytes"] / (d["ms"] / 1e3) / 1e9
-        kernels[kind] = {"GBs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                         "avg_ms_per_launch": round(d["ms"] / d["launches"], 4),
-                         "avg_bytes_per_launch": d["bytes"] // d["launches"], "launches": d["launches"]}
+    per_kind, kernels = kernel_table(timings, wl, widths)
     dominant = max(per_kind, key=lambda k: per_kind[k]["ms"])
     suffix = "_persistent" if args.persistent else "_direct"
     kname = {"pack": "k_pack", "unpack": "k_unpack", "replay": "k_adam"}[dominant] + suffix
@@ -883,7 +892,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
             side.synchronize()
             ms = e0.elapsed_time(e1)
             best = ms if best is None else min(best, ms)
-        out["drain"] = {"bound": "host-link", "slot": k, "bytes": nbytes, "ms": round(best, 3),
+        out["drain"] = {"bound": "host-link", "link": "PCIe Gen5 x16, 64 GB/s per direction in theory", "slot": k, "bytes": nbytes, "ms": round(best, 3),
                         "GBs": round(nbytes / (best / 1e3) / 1e9, 2)}
         ok = B.snapshot_peek(plan, k, host)["slot"] == k
         out["drain"]["header_ok"] = bool(ok)
