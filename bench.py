@@ -63,9 +63,10 @@ def parse_args():
     ap.add_argument("--adam-tile", type=int, default=0)
     ap.add_argument("--copy-blocks", type=int, default=0)
     ap.add_argument("--adam-blocks", type=int, default=0)
-    ap.add_argument("--alloc", default="tensor", choices=["flat", "tensor"], help="how the bench allocates the training state and the "
+    ap.add_argument("--alloc", default="tensor", choices=["flat", "tensor", "skewed"], help="how the bench allocates the training state and the "
                     "gradients: flat = one flat buffer per kind / per iteration with the tensors as views (what flat-partition "
-                    "optimizers do), tensor = every tensor its own allocation (the default).  The library sees pointers either way")
+                    "optimizers do), tensor = every tensor its own allocation (the default), skewed = flat with every kind starting at "
+                    "another offset inside a 64 KiB block.  The library sees pointers either way")
     ap.add_argument("--adam-shape", default="", help="one-tile-per-workgroup shape of the replay as THREADSxUNROLL, e.g. 64x2 "
                     "(default: the library's choice, 64x1 in the fp32 regime)")
     ap.add_argument("--nontemporal", type=int, default=-1)
@@ -89,6 +90,10 @@ def parse_args():
 # algorithmic bytes: what the method itself must move per slot and per replayed iteration
 # ---------------------------------------------------------------------------------------
 FP32_WIDTHS = (4, 4, 4, 2)                         # bytes per element of master, Adam m, Adam v, compute
+
+
+ALLOC_TEXT = {"tensor": "one allocation per tensor", "flat": "one flat buffer per kind",
+              "skewed": "one flat buffer per kind, the kinds at different offsets modulo 64 KiB"}
 
 
 def pack_bytes(wl, k, widths=FP32_WIDTHS):
@@ -403,7 +408,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
     wl = W.ep_rank_share()
     t_setup = time.time()
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
-    st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat")
+    st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat", skew=args.alloc == "skewed")
     state = B.State(st["master"], st["m"], st["v"], st["compute"])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order)
     apply_launch_knobs(args, plan, B)
@@ -447,7 +452,7 @@ def rank_share_bench(args, steps, warmup, torch, B, W, dev):
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"configs[3] {wl.name}", "state_allocation": "one flat buffer per kind" if args.alloc == "flat" else "one allocation per tensor", "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
+        "config": {"workload": f"configs[3] {wl.name}", "state_allocation": ALLOC_TEXT[args.alloc], "n_ops": wl.n_ops, "n_params": wl.n_params, "window": wl.window,
                    "step": "W x (snapshot_pack + restore_unpack) through one reused packed buffer, HBM-resident; no replay",
                    "step_algorithmic_bytes": step_bytes},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4), "kernels": kernels,
@@ -625,7 +630,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     log(f"[bench] workload {wl.name}: {wl.n_ops} operators, {wl.n_tensors} tensors, {wl.n_params / 1e9:.3f} B params, W={wl.window}")
     formats, d_scales = (0, 0, 0, 0), None
     if dtypes is None:
-        st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat")
+        st = W.make_state(wl, seed=args.seed, device=dev, flat=args.alloc == "flat", skew=args.alloc == "skewed")
     else:
         lib_fmt = {torch.float32: B.FMT_F32, torch.float16: B.FMT_F16, torch.bfloat16: B.FMT_BF16,
                    torch.float8_e4m3fn: B.FMT_E4M3, torch.float8_e5m2: B.FMT_E5M2}
@@ -638,7 +643,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     # operators skip their weight-gradient computation (Sec. 3.3), so their entries are None.
     grads = {}
     for i in range(wl.window):
-        grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev, flat=args.alloc == "flat",
+        grads[wl.t0 + i + 1] = W.make_grads(wl, wl.t0 + i + 1, seed=args.seed, device=dev, flat=args.alloc == "flat", skew=args.alloc == "skewed",
                                             only=[wl.slot_of_op[op] <= i for op, _ in wl.tensors])
     plan = B.ckpt_plan(wl.tensors, B.EXPLICIT, window=wl.window, slot_of_op=wl.slot_of_op, order=wl.order, formats=formats)
     apply_launch_knobs(args, plan, B)
@@ -720,7 +725,7 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
         "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"configs[{cfg[1]}] {wl.name}", "regime": args.regime, "element_bytes": list(widths),
-                   "state_allocation": "one flat buffer per kind" if args.alloc == "flat" else "one allocation per tensor",
+                   "state_allocation": ALLOC_TEXT[args.alloc],
                    "n_ops": wl.n_ops, "n_params": wl.n_params,
                    "window": wl.window, "step": "W x snapshot_pack + W x (restore_unpack + convert_replay), HBM-resident",
                    "step_algorithmic_bytes": step_bytes},

@@ -200,28 +200,34 @@ def make_state_tensor(wl: Workload, kind: str, t: int, seed: int = 0, device="cp
     return x.to(torch.bfloat16) if kind == "compute" else x
 
 
-def _flat_views(numels: Sequence[int], dtype: torch.dtype, device) -> List[torch.Tensor]:
-    """Views into ONE allocation, one per tensor, each starting on a 4 KiB boundary: the way flat-partition optimizers
-    (ZeRO-style) keep a kind of state.  Separate allocations per tensor and one flat buffer per kind are the same
-    to the library (it sees pointers); what differs is where the memory lands physically."""
+# Byte offsets (inside a 64 KiB block) at which the kinds of a `skew`ed state start: no two kinds are congruent modulo
+# 64 KiB, the situation of small tensors carved out of shared allocator blocks.
+SKEW_LEAD = {"master": 0, "m": 20 * 1024, "v": 40 * 1024 + 512, "compute": 12 * 1024, "grad": 52 * 1024 + 256}
+
+
+def _flat_views(numels: Sequence[int], dtype: torch.dtype, device, lead: int = 0) -> List[torch.Tensor]:
+    """Views into ONE allocation, one per tensor, each starting on a 4 KiB boundary (plus `lead` bytes): the way
+    flat-partition optimizers (ZeRO-style) keep a kind of state.  Separate allocations per tensor and one flat buffer
+    per kind are the same to the library (it sees pointers); what differs is where the memory lands physically."""
     width = torch.empty(0, dtype=dtype).element_size()
     seg = [(n * width + 4095) // 4096 * 4096 for n in numels]
-    flat = torch.empty(max(sum(seg), 1), dtype=torch.uint8, device=device)
-    out, off = [], 0
+    flat = torch.empty(max(sum(seg), 1) + lead, dtype=torch.uint8, device=device)
+    out, off = [], lead
     for n, sz in zip(numels, seg):
         out.append(flat[off: off + n * width].view(dtype))
         off += sz
     return out
 
 
-def make_state(wl: Workload, seed: int = 0, device="cpu", flat: bool = False) -> Dict[str, List[torch.Tensor]]:
+def make_state(wl: Workload, seed: int = 0, device="cpu", flat: bool = False, skew: bool = False) -> Dict[str, List[torch.Tensor]]:
     """master ~ N(0, std 0.02), m ~ N(0, std 1e-3), v = N(0, std 1e-3)^2 (so v >= 0),
     compute = bfloat16 copy of master.  One generator stream per (kind, tensor).  flat: every kind lives in one
-    flat buffer (same values)."""
+    flat buffer (same values); skew: flat, and every kind starts at another offset inside a 64 KiB block (SKEW_LEAD)."""
     st: Dict[str, List[torch.Tensor]] = {"master": [], "m": [], "v": [], "compute": []}
-    if flat:
+    if flat or skew:
         numels = [n for _, n in wl.tensors]
-        st = {k: _flat_views(numels, torch.bfloat16 if k == "compute" else torch.float32, device) for k in st}
+        st = {k: _flat_views(numels, torch.bfloat16 if k == "compute" else torch.float32, device,
+                             SKEW_LEAD[k] if skew else 0) for k in st}
         for t in range(wl.n_tensors):
             for k in ("master", "m", "v"):
                 st[k][t].copy_(make_state_tensor(wl, k, t, seed, device))
@@ -237,14 +243,15 @@ def make_state(wl: Workload, seed: int = 0, device="cpu", flat: bool = False) ->
 
 
 def make_grads(wl: Workload, step: int, seed: int = 0, device="cpu", flat: bool = False,
-               only: Optional[Sequence[bool]] = None) -> List[Optional[torch.Tensor]]:
+               only: Optional[Sequence[bool]] = None, skew: bool = False) -> List[Optional[torch.Tensor]]:
     """Gradients of iteration `step`: N(0, std 1e-3), fresh per (step, tensor).  With
     wl.heavy_tail an independent uniform draw marks 5% of the entries, which are scaled by 100.
     only[t] False: no gradient for tensor t (None in the result); flat: the gradients share one flat buffer."""
     want = [True] * wl.n_tensors if only is None else list(only)
     views = None
-    if flat:
-        views = iter(_flat_views([n for (_, n), w in zip(wl.tensors, want) if w], torch.float32, device))
+    if flat or skew:
+        views = iter(_flat_views([n for (_, n), w in zip(wl.tensors, want) if w], torch.float32, device,
+                                 SKEW_LEAD["grad"] if skew else 0))
     out: List[Optional[torch.Tensor]] = []
     for t, (_, n) in enumerate(wl.tensors):
         if not want[t]:
