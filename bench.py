@@ -9,11 +9,13 @@ algorithmic HBM bytes of a step divided by its wall time.  The device-to-host dr
 the host link, not by HBM; it is measured right after the timed steps and reported in its own
 object (it never enters `value`).
 
-Prints ONE JSON line.  Default workload: configs[1] (Mixtral-8x7B-shaped MoE layer), FP32 master weights and
-moments with bf16 compute weights; --config picks another workload, --regime stores the state as one of the
-low-precision regimes of Sec. 5.6.  Besides the contract's fields the line carries per-kernel figures
-(`kernels`), the fused conversion, the copy probe, the drain (whole and chunked), the upstream-log ring,
-a what-if (Algorithm 1 / recovery bounds / ETTR from the measured rates) and the oracle's CPU baseline.
+Prints ONE JSON line.  Default: configs[1] (Mixtral-8x7B-shaped MoE layer; FP32 master weights and moments with bf16
+compute weights) as the headline, then configs[2], [3] and [4] as complete results under `configs`; --config runs one
+workload alone, --regime stores the state as one of the low-precision regimes of Sec. 5.6.  Besides the contract's
+fields the line carries per-kernel figures (`kernels`), the fused conversion, the copy probe, the drain (whole and
+chunked), the upstream-log ring, a what-if (Algorithm 1 / recovery bounds / ETTR from the measured rates) and the
+oracle's CPU baseline.  --knob-sweep, --paired-tiles-sweep and --pair-distance-sweep add comparisons of the launch knobs
+made inside this one process (same tensors, same physical placement).
 """
 from __future__ import annotations
 
