@@ -48,7 +48,7 @@ def parse_args():
     ap.add_argument("--config", default="all", choices=["all", "c0", "c1", "c2", "c3", "c4"],
                     help="all (default): configs[1] is the headline (the contract's fields describe it) and the line also "
                          "carries configs[2], configs[3] and configs[4] under `configs`; cN: that workload alone")
-    ap.add_argument("--sub-steps", type=int, default=5, help="timed steps of each workload under `configs` (2 warm-up steps)")
+    ap.add_argument("--sub-steps", type=int, default=10, help="timed steps of each workload under `configs` (3 warm-up steps)")
     ap.add_argument("--regime", default="fp32", help="precision regime of the training state: fp32 (FP32 master weights and "
                     "moments, bf16 compute weights; the default) or one of the low-precision regimes of Sec. 5.6: "
                     "fp16_fp16_fp16+fp16, fp8_fp32_fp32+fp32, fp8_fp16_fp32+fp32, fp8_fp16_fp8+fp16, fp8_fp8_fp8+fp16 "
@@ -1052,7 +1052,7 @@ def main():
         out["configs"] = {}
         for cfg in todo[1:]:
             t0 = time.time()
-            sub = run(cfg, args.sub_steps, 2, False)
+            sub = run(cfg, args.sub_steps, 3, False)
             for key in ("metric", "n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
                 sub.pop(key, None)
             out["configs"][cfg] = sub
