@@ -203,6 +203,31 @@ def test_tune_knobs_validate():
             B.moev_tune(plan, knob, value)
 
 
+def test_mapping_and_pairing_knobs_validate():
+    """Workgroup -> tile mapping (0 off, 1 an eighth of the tiles per XCD, a power of two up to 65536 = chunk size) and
+    the piece distance of the paired replay tiles (0 off, 1 = the default 32 KiB, a power of two in [512, 4 MiB])."""
+    plan = _plan_of(W.tiny_moe())
+    assert B.moev_tune_get(plan, B.TUNE_XCD_REGIONS) == 1
+    assert B.moev_tune_get(plan, B.TUNE_COPY_XCD_REGIONS) == 64
+    assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == 32768
+    for knob in (B.TUNE_XCD_REGIONS, B.TUNE_COPY_XCD_REGIONS):
+        for good in (0, 1, 2, 64, 65536):
+            B.moev_tune(plan, knob, good)
+            assert B.moev_tune_get(plan, knob) == good
+        for bad in (-1, 3, 48, 131072):
+            with pytest.raises(B.MoevError) as e:
+                B.moev_tune(plan, knob, bad)
+            assert e.value.code == B.E_INVAL
+            assert B.moev_tune_get(plan, knob) == 65536     # a refused value changes nothing
+    for good, stored in ((0, 0), (1, 32768), (512, 512), (4 << 20, 4 << 20)):
+        B.moev_tune(plan, B.TUNE_PAIRED_TILES, good)
+        assert B.moev_tune_get(plan, B.TUNE_PAIRED_TILES) == stored
+    for bad in (-8, 2, 256, 3000, 8 << 20):
+        with pytest.raises(B.MoevError) as e:
+            B.moev_tune(plan, B.TUNE_PAIRED_TILES, bad)
+        assert e.value.code == B.E_INVAL
+
+
 def test_snapshot_peek_accepts_oracle_snapshot_and_rejects_others(orc):
     """The header the oracle writes is the header the library expects (format is shared by definition)."""
     import torch
