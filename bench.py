@@ -868,6 +868,16 @@ def window_bench(args, cfg, steps, warmup, extras, torch, B, W, dev):
     # the two directions); `frac` stays relative to the published 8 TB/s.
     if roofline["bound"] == "hbm":
         out["roofline"]["achieved_over_copy_probe"] = round(roofline["achieved"] / out["copy_probe"]["GBs"], 4)
+        # what the box's one-directional streams would allow for this kernel's read : write mix if the two directions did not
+        # disturb each other: bytes / (read bytes / read-only rate + written bytes / write-only rate)
+        if dominant == "replay":
+            rd = 4 + widths[0] + widths[1] + widths[2]
+            wr = widths[0] + widths[1] + widths[2] + widths[3]
+        else:
+            rd = wr = 1
+        mix = (rd + wr) / (rd / read_gbs + wr / write_gbs)
+        out["roofline"]["read_write_mix_bound_GBs"] = round(mix, 1)
+        out["roofline"]["achieved_over_read_write_mix_bound"] = round(roofline["achieved"] / mix, 4)
     if args.pair_distance_sweep:
         # the same copy with every wavefront instruction covering two 512-byte pieces D bytes apart (D = 512: consecutive)
         sweep = {}
