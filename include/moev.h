@@ -436,12 +436,13 @@ int uplog_stats(moev_uplog *log, uint64_t *entries, uint64_t *bytes_in_use, uint
  * pointers 16-byte aligned) with the same access shape as the gather kernel.  It is the
  * yardstick the pack/unpack throughput is compared with and the known-size kernel against
  * which HBM traffic counters are calibrated.  blocks = 0: one 4 KB tile per workgroup (the default
- * gather shape); blocks > 0: a fixed grid of that many workgroups, 32 KB per step. */
+ * gather shape, with the gather's default workgroup -> tile mapping: chunks of 64 tiles dealt to the XCDs round
+ * robin); blocks > 0: a fixed grid of that many workgroups, 32 KB per step. */
 int moev_copy_probe(void *d_dst, const void *d_src, size_t nbytes, uint32_t blocks, int nontemporal,
                     void *stream);
 
-/* moev_stream_probe: the one-directional companions of the copy probe, same access shape (one 4 KB tile per
- * workgroup).  mode 1: read nbytes from d_src and discard them (d_dst: 16 writable device bytes, which receive a
+/* moev_stream_probe: the one-directional companions of the copy probe, same access shape and mapping (one 4 KB tile
+ * per workgroup, chunks of 64 tiles per XCD).  mode 1: read nbytes from d_src and discard them (d_dst: 16 writable device bytes, which receive a
  * store only if the data happens to contain one particular 128-bit pattern); mode 2: fill d_dst[nbytes] with the
  * 32-bit `value`, d_src is not used.  nbytes a multiple of 16, pointers 16-byte aligned.  Read-only, write-only and
  * copy rates bracket what a kernel with a given read : write mix can reach on the box.

@@ -259,15 +259,25 @@ __global__ __launch_bounds__(kThreads) void k_unpack_persistent(MOEV_COPY_TABLES
 // plain contiguous copy: the yardstick for the gather/scatter kernels and the known-size
 // kernel against which the HBM traffic counters are calibrated
 // ------------------------------------------------------------------------------------
+// Workgroup -> tile mapping of the probes in their one-tile-per-workgroup form: the one pack and unpack use by default
+// (chunks of 64 tiles dealt to the XCDs round robin), so that the yardsticks are not handicapped against the kernels.
+constexpr uint32_t kProbeRegions = 64;
+
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void k_copy_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
                                                          uint64_t nbytes, uint32_t unroll) {
   const uint64_t row = static_cast<uint64_t>(kThreads) * kVec;
   const uint64_t chunk = row * unroll;
+  if (unroll == 1) {  // one 4 KB tile per workgroup
+    const uint32_t tile = tile_of_workgroup(blockIdx.x, static_cast<uint32_t>((nbytes + chunk - 1) / chunk), kProbeRegions);
+    if (tile == ~0u) return;
+    const uint64_t begin = tile * chunk;
+    pack_range<kThreads, 1, NT>(src, dst, begin, begin + chunk < nbytes ? begin + chunk : nbytes, nbytes);
+    return;
+  }
   for (uint64_t begin = blockIdx.x * chunk; begin < nbytes; begin += static_cast<uint64_t>(gridDim.x) * chunk) {
     const uint64_t end = begin + chunk < nbytes ? begin + chunk : nbytes;
-    if (unroll == 1) pack_range<kThreads, 1, NT>(src, dst, begin, end, nbytes);
-    else pack_range<kThreads, 8, NT>(src, dst, begin, end, nbytes);
+    pack_range<kThreads, 8, NT>(src, dst, begin, end, nbytes);
   }
 }
 
@@ -277,7 +287,9 @@ __global__ __launch_bounds__(kThreads) void k_copy_probe(const uint8_t* __restri
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void k_read_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ sink,
                                                          uint64_t nbytes) {
-  const uint64_t o = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * kVec;
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec)), kProbeRegions);
+  if (tile == ~0u) return;
+  const uint64_t o = (static_cast<uint64_t>(tile) * kThreads + threadIdx.x) * kVec;
   if (o + kVec > nbytes) return;
   const u32x4 r = ld<NT>(reinterpret_cast<const u32x4*>(src + o));
   // keeps the load alive: a store that needs two 32-bit coincidences in the data
@@ -286,7 +298,9 @@ __global__ __launch_bounds__(kThreads) void k_read_probe(const uint8_t* __restri
 
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void k_write_probe(uint8_t* __restrict__ dst, uint64_t nbytes, uint32_t value) {
-  const uint64_t o = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * kVec;
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec)), kProbeRegions);
+  if (tile == ~0u) return;
+  const uint64_t o = (static_cast<uint64_t>(tile) * kThreads + threadIdx.x) * kVec;
   if (o + kVec > nbytes) return;
   st<NT>(reinterpret_cast<u32x4*>(dst + o), u32x4{value, value, value, value});
 }
@@ -300,7 +314,9 @@ __global__ __launch_bounds__(kThreads) void k_write_probe(uint8_t* __restrict__ 
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void k_pair_probe(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
                                                          uint64_t nbytes, uint32_t dist_log2) {
-  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec)), kProbeRegions);
+  if (tile == ~0u) return;
+  const uint64_t wave = static_cast<uint64_t>(tile) * (kThreads / 64) + (threadIdx.x >> 6);
   const uint32_t lane = threadIdx.x & 63;
   const uint64_t per_block = 1ull << (dist_log2 - 9);
   const uint64_t o = (wave / per_block) * (2ull << dist_log2) + (static_cast<uint64_t>(lane >> 5) << dist_log2) +
@@ -314,7 +330,8 @@ __global__ __launch_bounds__(kThreads) void k_pair_probe(const uint8_t* __restri
 // ------------------------------------------------------------------------------------
 hipError_t launch_stream_probe(int mode, const void* src, void* dst, uint64_t nbytes, uint32_t value, bool nontemporal,
                                hipStream_t s) {
-  const uint32_t blocks = static_cast<uint32_t>((nbytes + kThreads * kVec - 1) / (kThreads * kVec));
+  const uint32_t unit = 8 * kProbeRegions;  // the chunked mapping deals whole rounds of chunks
+  const uint32_t blocks = static_cast<uint32_t>(((nbytes + kThreads * kVec - 1) / (kThreads * kVec) + unit - 1) / unit * unit);
   const uint8_t* sp = static_cast<const uint8_t*>(src);
   uint8_t* dp = static_cast<uint8_t*>(dst);
   if (mode == 3) {   // value = log2 of the distance between the two pieces of a wavefront
@@ -340,6 +357,7 @@ hipError_t launch_copy_probe(const void* src, void* dst, uint64_t nbytes, uint32
                              bool nontemporal, hipStream_t s) {
   const uint8_t* sp = static_cast<const uint8_t*>(src);
   uint8_t* dp = static_cast<uint8_t*>(dst);
+  if (unroll == 1) blocks = (blocks + 8 * kProbeRegions - 1) / (8 * kProbeRegions) * (8 * kProbeRegions);
   if (nontemporal) hipLaunchKernelGGL(k_copy_probe<true>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, unroll);
   else hipLaunchKernelGGL(k_copy_probe<false>, dim3(blocks), dim3(kThreads), 0, s, sp, dp, nbytes, unroll);
   return hipGetLastError();
